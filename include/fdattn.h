@@ -1,0 +1,164 @@
+/*
+ * libfdattn -- decode-phase attention with asynchronized softmax for MI355X.
+ *
+ * C-ABI boundary of the library.  The method is Section 3 of FlashDecoding++
+ * (arXiv 2311.01282): one query token per sequence attends over an fp16 KV
+ * cache; the sequence axis is cut into chunks ("partial vectors"); every chunk
+ * accumulates e^{x - phi} and e^{x - phi} v against ONE unified scaling factor
+ * phi, so chunk results simply add (Eq. 3, Eq. 4); a chunk whose logits leave
+ * a < x - phi < b raises a flag and the whole row is recomputed with the
+ * synchronized partial softmax of Eq. 2 (Section 3, "Recomputation").
+ *
+ * Conventions common to every call
+ * --------------------------------
+ * Memory.  Every data pointer is DEVICE memory allocated and owned by the
+ *   caller (hipMalloc or a framework tensor).  The library allocates nothing,
+ *   frees nothing and keeps no state between calls.  Inputs are never written.
+ * Layouts (all contiguous, row-major, IEEE binary16 unless noted):
+ *   q        [batch, n_q_heads, head_dim]
+ *   k_cache  [batch, n_kv_heads, max_seq, head_dim]
+ *   v_cache  [batch, n_kv_heads, max_seq, head_dim]
+ *   seq_lens [batch] int32 -- valid keys per sequence; values are clamped to
+ *            [0, max_seq]; cache positions >= the valid length are padding and
+ *            are never read.  A sequence of length 0 produces a zero row and
+ *            raises no flag.
+ *   out      [batch, n_q_heads, head_dim]
+ *   All pointers must be 16-byte aligned.
+ *   Query head hq reads KV head hq / (n_q_heads / n_kv_heads).
+ * Logit.  x_j = scale * <q, k_j> (fp32 accumulation); phi and the bounds apply
+ *   to this scaled logit.  A "row" is one (sequence, query head) pair; chunk c
+ *   of a row covers keys [c*chunk, min((c+1)*chunk, valid length)).
+ * Stream.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *   stream).  All work is enqueued on it; no call synchronizes or reads device
+ *   memory on the host.  Results are ready when the stream reaches that point.
+ * Errors.  Every entry point returns an fd_status.  Problems visible on the host
+ *   (null pointer, unsupported shape, bad bounds, workspace too small) are
+ *   reported before anything is enqueued.  A failed launch returns FD_ERR_HIP.
+ * Threads.  Calls are re-entrant as long as they use distinct workspaces.
+ * Supported shapes.  head_dim == 128; chunk in {64, 128, 256, 512, 1024};
+ *   n_q_heads a multiple of n_kv_heads; batch*n_q_heads*ceil(max_seq/chunk)
+ *   < 2^31.
+ */
+#ifndef FDATTN_H
+#define FDATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FD_OK = 0,
+    FD_ERR_NULL = 1,         /* a required pointer is NULL                      */
+    FD_ERR_SHAPE = 2,        /* non-positive size, heads not divisible, ...     */
+    FD_ERR_BOUNDS = 3,       /* lo >= hi, or phi / a bound is NaN or infinite   */
+    FD_ERR_WORKSPACE = 4,    /* workspace NULL, misaligned or too small         */
+    FD_ERR_UNSUPPORTED = 5,  /* valid in principle, not built (head_dim, chunk) */
+    FD_ERR_HIP = 6           /* the HIP runtime refused a launch                */
+} fd_status;
+
+/* Problem shape.  Plain data, read during the call only. */
+typedef struct {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t max_seq;   /* padded length of the cache's sequence axis           */
+    int32_t chunk;     /* keys per partial vector                              */
+    float   scale;     /* logit scale, e.g. 1/sqrt(head_dim)                   */
+} fd_shape;
+
+/* Bounds a, b on (logit - phi): in range means lo < x - phi < hi, strictly.
+ * Equality with either bound, either side out of range, or a NaN logit flags. */
+typedef struct { float lo, hi; } fd_bounds;
+
+/* Caller-owned device scratch of at least fd_workspace_bytes(shape) bytes,
+ * 256-byte aligned.  Contents before the call are irrelevant; after a call it
+ * holds that call's partial results and flags (see fd_get_flags).             */
+typedef struct { void *ptr; size_t bytes; } fd_workspace;
+
+/* Bytes of workspace the calls below need for this shape; 0 if the shape is
+ * invalid or unsupported.  Pure host function.                                */
+size_t fd_workspace_bytes(const fd_shape *shape);
+
+/*
+ * Asynchronized-softmax decode attention, one row at a time (Section 3).
+ *   1. per (row, chunk): logits, range guard, sum e^{x-phi} and sum e^{x-phi} v
+ *      with no maximum and no rescaling              (Eq. 4, inner sums)
+ *   2. chunk flags -> row flags, list and count of flagged rows, on the device
+ *   3. unflagged rows: out = (sum of numerators) / (sum of denominators)
+ *                                                    (Eq. 4, outer sums)
+ *   4. flagged rows only: recomputed by the synchronized partial softmax --
+ *      per chunk (m, l, f.V), merged with e^{m_c - m} -- and written to out
+ *                                                    (Eq. 2; "Recomputation")
+ * Works for any head grouping (each query head is an independent row).
+ */
+fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *seq_lens, float phi,
+                         fd_bounds bounds, void *out, fd_workspace ws, void *stream);
+
+/*
+ * Same result as fd_decode_attn for grouped-query attention: the
+ * n_q_heads / n_kv_heads query heads that share one KV head are processed
+ * together so each K and V element is read from memory once per group.
+ * Requires 2 <= n_q_heads / n_kv_heads <= 16.  (Grouping is not in the paper;
+ * per query head the arithmetic is Eq. 4 unchanged.)  Flags are per query head.
+ */
+fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *seq_lens, float phi,
+                             fd_bounds bounds, void *out, fd_workspace ws, void *stream);
+
+/*
+ * The synchronized partial softmax (Eq. 2) applied to EVERY row: step 4 above
+ * without steps 1-3.  This is the scheme the paper's method replaces; it is the
+ * in-library baseline and the cross-check for the unified path.  No phi, no
+ * bounds, no flags.
+ */
+fd_status fd_decode_attn_sync(const fd_shape *shape, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *seq_lens,
+                              void *out, fd_workspace ws, void *stream);
+
+/*
+ * Step 1 of fd_decode_attn alone (Eq. 4, inner sums and the range guard):
+ * fills the workspace's per-chunk numerators, denominators and chunk flags and
+ * writes nothing else.  For tests of the partial sums and for timing the
+ * dominant kernel on its own.
+ */
+fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const void *k_cache,
+                                 const void *v_cache, const int32_t *seq_lens, float phi,
+                                 fd_bounds bounds, fd_workspace ws, void *stream);
+
+/*
+ * Device pointers into `ws` to the flags of the last fd_decode_attn /
+ * fd_decode_attn_gqa call that used it (valid until the next call on `ws`):
+ *   chunk_flags [batch*n_q_heads, ceil(max_seq/chunk)] uint8, 0 or 1
+ *   row_flags   [batch*n_q_heads] uint8 = OR over the row's chunks
+ *   n_flagged   [1] int32 = number of flagged rows
+ *   flagged_rows[batch*n_q_heads] int32, the first *n_flagged entries are the
+ *               flagged row indices in ascending order
+ * Any output pointer may be NULL.  After fd_decode_attn_partial only
+ * chunk_flags is meaningful.
+ */
+fd_status fd_get_flags(const fd_shape *shape, fd_workspace ws,
+                       const uint8_t **chunk_flags, const uint8_t **row_flags,
+                       const int32_t **n_flagged, const int32_t **flagged_rows);
+
+/*
+ * Device pointers into `ws` to the per-chunk partial results (D3 of Eq. 4):
+ *   num [batch*n_q_heads, ceil(max_seq/chunk), head_dim] fp32 = sum e^{x-phi} v
+ *   den [batch*n_q_heads, ceil(max_seq/chunk)]           fp32 = sum e^{x-phi}
+ * Chunks without a valid key hold zeros.  Rows that were recomputed hold the
+ * synchronized scheme's (f.V, l) instead.
+ */
+fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
+                          const float **num, const float **den);
+
+/* Static, human-readable name of a status code. */
+const char *fd_status_str(fd_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDATTN_H */

@@ -1,0 +1,231 @@
+// C-ABI entry points of libfdattn: argument checks, workspace carving, launch order.
+#include "../../include/fdattn.h"
+#include "fd_internal.h"
+
+#include <cmath>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t num, den, mloc, chunk_flags, row_flags, list, count, total;
+    long long rows, nc;
+};
+
+// FD_OK and a filled layout, or the reason the shape cannot be served.
+fd_status plan(const fd_shape *sh, Layout *L)
+{
+    if (!sh) return FD_ERR_NULL;
+    if (sh->batch < 0 || sh->n_q_heads <= 0 || sh->n_kv_heads <= 0 || sh->head_dim <= 0 ||
+        sh->max_seq <= 0 || sh->chunk <= 0)
+        return FD_ERR_SHAPE;
+    if (sh->n_q_heads % sh->n_kv_heads != 0) return FD_ERR_SHAPE;
+    if (!std::isfinite(sh->scale)) return FD_ERR_SHAPE;
+    if (sh->head_dim != fd::kHeadDim) return FD_ERR_UNSUPPORTED;
+    switch (sh->chunk) {
+        case 64: case 128: case 256: case 512: case 1024: break;
+        default: return FD_ERR_UNSUPPORTED;
+    }
+    const long long rows = (long long)sh->batch * sh->n_q_heads;
+    const long long nc = ((long long)sh->max_seq + sh->chunk - 1) / sh->chunk;
+    if (rows * nc >= (1ll << 31)) return FD_ERR_UNSUPPORTED;
+    const size_t slots = (size_t)(rows * nc);
+    size_t off = 0;
+    L->num = off;          off = align_up(off + slots * fd::kHeadDim * sizeof(float));
+    L->den = off;          off = align_up(off + slots * sizeof(float));
+    L->mloc = off;         off = align_up(off + slots * sizeof(float));
+    L->chunk_flags = off;  off = align_up(off + slots);
+    L->row_flags = off;    off = align_up(off + (size_t)rows);
+    L->list = off;         off = align_up(off + (size_t)rows * sizeof(int32_t));
+    L->count = off;        off = align_up(off + sizeof(int32_t));
+    L->total = off;
+    L->rows = rows;
+    L->nc = nc;
+    return FD_OK;
+}
+
+fd_status check_ws(const Layout &L, fd_workspace ws)
+{
+    if (!ws.ptr || ((uintptr_t)ws.ptr % kAlign) != 0 || ws.bytes < L.total) return FD_ERR_WORKSPACE;
+    return FD_OK;
+}
+
+fd::WsView view(const Layout &L, fd_workspace ws)
+{
+    char *base = static_cast<char *>(ws.ptr);
+    fd::WsView w;
+    w.num = reinterpret_cast<float *>(base + L.num);
+    w.den = reinterpret_cast<float *>(base + L.den);
+    w.mloc = reinterpret_cast<float *>(base + L.mloc);
+    w.chunk_flags = reinterpret_cast<uint8_t *>(base + L.chunk_flags);
+    w.row_flags = reinterpret_cast<uint8_t *>(base + L.row_flags);
+    w.list = reinterpret_cast<int32_t *>(base + L.list);
+    w.count = reinterpret_cast<int32_t *>(base + L.count);
+    return w;
+}
+
+inline bool misaligned(const void *p) { return ((uintptr_t)p % 16) != 0; }
+
+fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const void *v,
+                       const int32_t *seq_lens, void *out, bool need_out, fd_workspace ws,
+                       fd::Problem *p)
+{
+    Layout L;
+    fd_status st = plan(sh, &L);
+    if (st != FD_OK) return st;
+    if (!q || !k || !v || !seq_lens || (need_out && !out)) return FD_ERR_NULL;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || (need_out && misaligned(out)) ||
+        ((uintptr_t)seq_lens % 4) != 0)
+        return FD_ERR_SHAPE;
+    st = check_ws(L, ws);
+    if (st != FD_OK) return st;
+    p->q = static_cast<const uint16_t *>(q);
+    p->k = static_cast<const uint16_t *>(k);
+    p->v = static_cast<const uint16_t *>(v);
+    p->seq_lens = seq_lens;
+    p->out = static_cast<uint16_t *>(out);
+    p->ws = view(L, ws);
+    p->B = sh->batch; p->Hq = sh->n_q_heads; p->Hkv = sh->n_kv_heads;
+    p->G = sh->n_q_heads / sh->n_kv_heads;
+    p->Smax = sh->max_seq; p->C = sh->chunk; p->nc = (int)L.nc; p->rows = (int)L.rows;
+    p->scale = sh->scale; p->phi = 0.f; p->lo = 0.f; p->hi = 0.f;
+    return FD_OK;
+}
+
+fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
+{
+    if (!std::isfinite(phi) || !std::isfinite(b.lo) || !std::isfinite(b.hi) || !(b.lo < b.hi))
+        return FD_ERR_BOUNDS;
+    p->phi = phi; p->lo = b.lo; p->hi = b.hi;
+    return FD_OK;
+}
+
+#define FD_TRY(expr) do { if ((expr) != hipSuccess) return FD_ERR_HIP; } while (0)
+
+// Steps 2-4 shared by the per-row and the grouped entry points.
+fd_status finish_unified(const fd::Problem &p, hipStream_t s)
+{
+    FD_TRY(fd::launch_flag_reduce(p, s));
+    FD_TRY(fd::launch_combine_unified(p, s));
+    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/true, s));
+    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/true, s));
+    return FD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fd_workspace_bytes(const fd_shape *shape)
+{
+    Layout L;
+    return plan(shape, &L) == FD_OK ? L.total : 0;
+}
+
+fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const void *k_cache,
+                                 const void *v_cache, const int32_t *seq_lens, float phi,
+                                 fd_bounds bounds, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, nullptr, false, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (p.rows == 0) return FD_OK;
+    FD_TRY(fd::launch_partial_unified(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
+fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cache,
+                         const void *v_cache, const int32_t *seq_lens, float phi,
+                         fd_bounds bounds, void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (p.rows == 0) return FD_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FD_TRY(fd::launch_partial_unified(p, s));
+    return finish_unified(p, s);
+}
+
+fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *seq_lens, float phi,
+                             fd_bounds bounds, void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (p.G < 2 || p.G > 16) return FD_ERR_UNSUPPORTED;
+    if (p.rows == 0) return FD_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FD_TRY(fd::launch_partial_unified_gqa(p, s));
+    return finish_unified(p, s);
+}
+
+fd_status fd_decode_attn_sync(const fd_shape *shape, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *seq_lens,
+                              void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    if (p.rows == 0) return FD_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/false, s));
+    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/false, s));
+    return FD_OK;
+}
+
+fd_status fd_get_flags(const fd_shape *shape, fd_workspace ws,
+                       const uint8_t **chunk_flags, const uint8_t **row_flags,
+                       const int32_t **n_flagged, const int32_t **flagged_rows)
+{
+    Layout L;
+    fd_status st = plan(shape, &L);
+    if (st != FD_OK) return st;
+    st = check_ws(L, ws);
+    if (st != FD_OK) return st;
+    const fd::WsView w = view(L, ws);
+    if (chunk_flags) *chunk_flags = w.chunk_flags;
+    if (row_flags) *row_flags = w.row_flags;
+    if (n_flagged) *n_flagged = w.count;
+    if (flagged_rows) *flagged_rows = w.list;
+    return FD_OK;
+}
+
+fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
+                          const float **num, const float **den)
+{
+    Layout L;
+    fd_status st = plan(shape, &L);
+    if (st != FD_OK) return st;
+    st = check_ws(L, ws);
+    if (st != FD_OK) return st;
+    const fd::WsView w = view(L, ws);
+    if (num) *num = w.num;
+    if (den) *den = w.den;
+    return FD_OK;
+}
+
+const char *fd_status_str(fd_status status)
+{
+    switch (status) {
+        case FD_OK: return "FD_OK";
+        case FD_ERR_NULL: return "FD_ERR_NULL: a required pointer is NULL";
+        case FD_ERR_SHAPE: return "FD_ERR_SHAPE: invalid shape, scale or pointer alignment";
+        case FD_ERR_BOUNDS: return "FD_ERR_BOUNDS: need finite phi and lo < hi";
+        case FD_ERR_WORKSPACE: return "FD_ERR_WORKSPACE: workspace NULL, misaligned or too small";
+        case FD_ERR_UNSUPPORTED: return "FD_ERR_UNSUPPORTED: shape not supported by this build";
+        case FD_ERR_HIP: return "FD_ERR_HIP: the HIP runtime refused a launch";
+    }
+    return "unknown fd_status";
+}
+
+}  // extern "C"

@@ -1,0 +1,50 @@
+// Internal declarations shared by the libfdattn translation units (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fd {
+
+constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
+constexpr int kThreads = 256;      // 4 wavefronts per workgroup in the chunk kernels
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Views into the caller's workspace.
+struct WsView {
+    float   *num;          // [rows, nc, 128]  sum e^{x-phi} v   (or f.V of the synchronized scheme)
+    float   *den;          // [rows, nc]       sum e^{x-phi}     (or l)
+    float   *mloc;         // [rows, nc]       chunk maximum m (synchronized scheme only)
+    uint8_t *chunk_flags;  // [rows, nc]
+    uint8_t *row_flags;    // [rows]
+    int32_t *list;         // [rows]  flagged rows, ascending
+    int32_t *count;        // [1]     number of flagged rows
+};
+
+struct Problem {
+    const uint16_t *q, *k, *v;
+    const int32_t  *seq_lens;
+    uint16_t       *out;
+    WsView ws;
+    int B, Hq, Hkv, G, Smax, C, nc, rows;
+    float scale, phi, lo, hi;
+};
+
+__device__ __forceinline__ int valid_len(const Problem &p, int b)
+{
+    int S = p.seq_lens[b];
+    S = S < 0 ? 0 : S;
+    return S > p.Smax ? p.Smax : S;
+}
+
+// fd_row_kernels.hip : one query head per workgroup (VALU path)
+hipError_t launch_partial_unified(const Problem &p, hipStream_t s);
+hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s);
+// fd_reduce_kernels.hip : flag reduction and the two combines
+hipError_t launch_flag_reduce(const Problem &p, hipStream_t s);
+hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
+hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
+// fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
+hipError_t launch_partial_unified_gqa(const Problem &p, hipStream_t s);
+
+}  // namespace fd

@@ -1,0 +1,121 @@
+"""ctypes binding of libfdattn: argument marshalling only.
+
+Every function takes device pointers as Python ints (e.g. ``tensor.data_ptr()``)
+and a ``Shape``; all arithmetic runs in the library's HIP kernels.  There is no
+CPU fallback: if the compiled library is missing, importing this module raises.
+Names mirror ``include/fdattn.h``.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfdattn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libfdattn.so is not built: run `python -m paper_2311_01282_amd.build` "
+        "(or __graft_entry__.build()) first; there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+FD_OK, FD_ERR_NULL, FD_ERR_SHAPE, FD_ERR_BOUNDS, FD_ERR_WORKSPACE, FD_ERR_UNSUPPORTED, FD_ERR_HIP = range(7)
+
+
+class Shape(ctypes.Structure):
+    """fd_shape"""
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("max_seq", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("scale", ctypes.c_float)]
+
+
+class Bounds(ctypes.Structure):
+    """fd_bounds"""
+    _fields_ = [("lo", ctypes.c_float), ("hi", ctypes.c_float)]
+
+
+class Workspace(ctypes.Structure):
+    """fd_workspace"""
+    _fields_ = [("ptr", ctypes.c_void_p), ("bytes", ctypes.c_size_t)]
+
+
+class FdError(RuntimeError):
+    def __init__(self, status):
+        self.status = int(status)
+        super().__init__(status_str(status))
+
+
+_vp, _f = ctypes.c_void_p, ctypes.c_float
+_sp = ctypes.POINTER(Shape)
+_lib.fd_workspace_bytes.restype = ctypes.c_size_t
+_lib.fd_workspace_bytes.argtypes = [_sp]
+_lib.fd_status_str.restype = ctypes.c_char_p
+_lib.fd_status_str.argtypes = [ctypes.c_int]
+for _name in ("fd_decode_attn", "fd_decode_attn_gqa"):
+    getattr(_lib, _name).restype = ctypes.c_int
+    getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+_lib.fd_decode_attn_sync.restype = ctypes.c_int
+_lib.fd_decode_attn_sync.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, Workspace, _vp]
+_lib.fd_decode_attn_partial.restype = ctypes.c_int
+_lib.fd_decode_attn_partial.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, Workspace, _vp]
+_lib.fd_get_flags.restype = ctypes.c_int
+_lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
+_lib.fd_get_partials.restype = ctypes.c_int
+_lib.fd_get_partials.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 2
+
+EXPORTS = ("fd_workspace_bytes", "fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_sync",
+           "fd_decode_attn_partial", "fd_get_flags", "fd_get_partials", "fd_status_str")
+
+
+def status_str(status):
+    return _lib.fd_status_str(int(status)).decode()
+
+
+def _check(status):
+    if status != FD_OK:
+        raise FdError(status)
+
+
+def make_shape(batch, n_q_heads, n_kv_heads, head_dim, max_seq, chunk, scale):
+    return Shape(int(batch), int(n_q_heads), int(n_kv_heads), int(head_dim), int(max_seq),
+                 int(chunk), float(scale))
+
+
+def fd_workspace_bytes(shape):
+    return int(_lib.fd_workspace_bytes(ctypes.byref(shape)))
+
+
+def fd_decode_attn(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                               Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_gqa(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_gqa(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                                   Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_sync(shape, q, k_cache, v_cache, seq_lens, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_sync(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, out,
+                                    Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_partial(shape, q, k_cache, v_cache, seq_lens, phi, bounds, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_partial(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                                       Bounds(*bounds), Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_get_flags(shape, ws_ptr, ws_bytes):
+    """Device addresses (ints) of chunk_flags, row_flags, n_flagged, flagged_rows."""
+    outs = [ctypes.c_void_p() for _ in range(4)]
+    _check(_lib.fd_get_flags(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes),
+                             *[ctypes.byref(o) for o in outs]))
+    return tuple(o.value for o in outs)
+
+
+def fd_get_partials(shape, ws_ptr, ws_bytes):
+    """Device addresses (ints) of num and den."""
+    outs = [ctypes.c_void_p() for _ in range(2)]
+    _check(_lib.fd_get_partials(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes),
+                                *[ctypes.byref(o) for o in outs]))
+    return tuple(o.value for o in outs)

@@ -155,6 +155,16 @@ fd_status fd_get_flags(const fd_shape *shape, fd_workspace ws,
 fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
                           const float **num, const float **den);
 
+/*
+ * Measurement aid, not part of the method: enqueue a plain streaming read of two
+ * device buffers of `bytes_each` bytes each (a multiple of 65536) with the same
+ * launch geometry as the chunk kernel and no arithmetic.  `sink` is 4 bytes of
+ * device memory (practically never written).  Timing this gives the read rate a
+ * kernel of that shape can reach on the device at hand.
+ */
+fd_status fd_probe_stream_read(const void *a, const void *b, size_t bytes_each,
+                               void *sink, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *fd_status_str(fd_status status);
 

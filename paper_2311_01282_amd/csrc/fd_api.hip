@@ -214,6 +214,16 @@ fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
     return FD_OK;
 }
 
+fd_status fd_probe_stream_read(const void *a, const void *b, size_t bytes_each,
+                               void *sink, void *stream)
+{
+    if (!a || !b || !sink) return FD_ERR_NULL;
+    if (bytes_each % 65536 != 0 || misaligned(a) || misaligned(b)) return FD_ERR_SHAPE;
+    FD_TRY(fd::launch_stream_read(a, b, bytes_each, static_cast<unsigned *>(sink),
+                                  static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
 const char *fd_status_str(fd_status status)
 {
     switch (status) {

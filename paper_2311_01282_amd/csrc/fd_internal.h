@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace fd {
 
 constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
@@ -37,6 +39,16 @@ __device__ __forceinline__ int valid_len(const Problem &p, int b)
     return S > p.Smax ? p.Smax : S;
 }
 
+// Launch that reports its own error code (the runtime's "last error" slot is shared
+// with every other HIP user in the process and may hold a stale, unrelated value).
+template <typename... KArgs>
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
+                         typename std::common_type<KArgs>::type... args)
+{
+    void *argv[] = {static_cast<void *>(&args)...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, 0, s);
+}
+
 // fd_row_kernels.hip : one query head per workgroup (VALU path)
 hipError_t launch_partial_unified(const Problem &p, hipStream_t s);
 hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s);
@@ -46,5 +58,7 @@ hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
 hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
 hipError_t launch_partial_unified_gqa(const Problem &p, hipStream_t s);
+// fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling
+hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, unsigned *sink, hipStream_t s);
 
 }  // namespace fd

@@ -95,23 +95,20 @@ __global__ __launch_bounds__(kHeadDim) void combine_sync_kernel(const Problem p,
 
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s)
 {
-    flag_reduce_kernel<<<dim3(1), dim3(1024), 0, s>>>(p);
-    return hipGetLastError();
+    return launch(flag_reduce_kernel, dim3(1), dim3(1024), s, p);
 }
 
 hipError_t launch_combine_unified(const Problem &p, hipStream_t s)
 {
     if (p.rows == 0) return hipSuccess;
-    combine_unified_kernel<<<dim3(p.rows), dim3(kHeadDim), 0, s>>>(p);
-    return hipGetLastError();
+    return launch(combine_unified_kernel, dim3(p.rows), dim3(kHeadDim), s, p);
 }
 
 hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s)
 {
     if (p.rows == 0) return hipSuccess;
     const int grid = use_list ? (p.rows < 512 ? p.rows : 512) : p.rows;
-    combine_sync_kernel<<<dim3(grid), dim3(kHeadDim), 0, s>>>(p, use_list ? 1 : 0);
-    return hipGetLastError();
+    return launch(combine_sync_kernel, dim3(grid), dim3(kHeadDim), s, p, use_list ? 1 : 0);
 }
 
 }  // namespace fd

@@ -261,8 +261,7 @@ template <int C> struct UnifiedLauncher {
     {
         const unsigned grid = (unsigned)((long long)p.rows * p.nc);
         if (grid == 0) return hipSuccess;
-        partial_unified_kernel<C><<<dim3(grid), dim3(kThreads), 0, s>>>(p);
-        return hipGetLastError();
+        return launch(partial_unified_kernel<C>, dim3(grid), dim3(kThreads), s, p);
     }
 };
 
@@ -273,8 +272,7 @@ template <int C> struct SyncLauncher {
         if (all == 0) return hipSuccess;
         const long long cap = 4096;             // resident capacity is 256 CUs x a few workgroups
         const unsigned grid = (unsigned)(use_list ? (all < cap ? all : cap) : all);
-        partial_sync_kernel<C><<<dim3(grid), dim3(kThreads), 0, s>>>(p, use_list ? 1 : 0);
-        return hipGetLastError();
+        return launch(partial_sync_kernel<C>, dim3(grid), dim3(kThreads), s, p, use_list ? 1 : 0);
     }
 };
 

@@ -63,8 +63,12 @@ _lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
 _lib.fd_get_partials.restype = ctypes.c_int
 _lib.fd_get_partials.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 2
 
+_lib.fd_probe_stream_read.restype = ctypes.c_int
+_lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
+
 EXPORTS = ("fd_workspace_bytes", "fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_sync",
-           "fd_decode_attn_partial", "fd_get_flags", "fd_get_partials", "fd_status_str")
+           "fd_decode_attn_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
+           "fd_status_str")
 
 
 def status_str(status):
@@ -119,3 +123,7 @@ def fd_get_partials(shape, ws_ptr, ws_bytes):
     _check(_lib.fd_get_partials(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes),
                                 *[ctypes.byref(o) for o in outs]))
     return tuple(o.value for o in outs)
+
+
+def fd_probe_stream_read(a, b, bytes_each, sink, stream=0):
+    _check(_lib.fd_probe_stream_read(a, b, bytes_each, sink, stream))

@@ -61,3 +61,83 @@ def test_partial_sums_match_eq4(oracle, H, chunk):
     np.testing.assert_allclose(den, oden, rtol=2e-5, atol=0)
     np.testing.assert_allclose(num, onum, rtol=0, atol=2e-5 * np.abs(oden).max())
     assert not dc.chunk_flags().any()
+
+
+def test_planted_keys_flag_and_recompute(oracle, H):
+    """Rows holding a key whose logit exceeds phi + hi are flagged (exactly the
+    chunk that holds it), listed in ascending order and recomputed; all rows match."""
+    case = synth.make_case(B=3, Hq=4, Hkv=4, D=128, Smax=2048, seed=300, seq_lens=[2048, 1500, 300],
+                           poison_padding=True)
+    planted = synth.plant_keys(case, 3, 36.0, seed=301)
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, 256)
+    assert margin.min() > 1e-2 and orf.sum() == 3
+    dc = H.DeviceCase(case, chunk=256)
+    got = dc.run("fd_decode_attn")
+    H.assert_close(got, want, "unified + recompute")
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+    assert n == 3 and rows.tolist() == sorted(b * 4 + h for b, h, _ in planted)
+    for b, h, pos in planted:                      # closed form: the row is its planted key's V row
+        np.testing.assert_allclose(got[b, h], case["v"][b, h, pos].astype(np.float64), atol=2e-3)
+    # gamma = 12 stays inside the bounds: nothing may be flagged
+    case2 = synth.make_case(B=3, Hq=4, Hkv=4, D=128, Smax=2048, seed=300, seq_lens=[2048, 1500, 300])
+    synth.plant_keys(case2, 3, 12.0, seed=301)
+    dc2 = H.DeviceCase(case2, chunk=256)
+    got2 = dc2.run("fd_decode_attn")
+    H.assert_close(got2, exact(oracle, case2), "gamma 12")
+    assert dc2.flags()[2] == 0
+
+
+def test_every_row_flagged_and_lower_bound(oracle, H):
+    """Tight bounds flag every row (both sides of the guard): the whole output then
+    comes from the synchronized scheme."""
+    case = synth.make_case(B=2, Hq=3, Hkv=3, D=128, Smax=900, seed=310, seq_lens=[900, 257])
+    want = exact(oracle, case)
+    dc = H.DeviceCase(case, chunk=128)
+    for phi, bounds in ((3.0, (-1.5, 20.0)), (0.0, (-60.0, 0.75)), (0.0, (-0.5, 0.5))):
+        ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], phi,
+                                        bounds[0], bounds[1], 128)
+        got = dc.run("fd_decode_attn", phi=phi, bounds=bounds)
+        cf, rf, n, rows = dc.flags()
+        near = margin.min() <= 1e-4     # a logit within rounding distance of a bound: flags not comparable
+        assert near or (np.array_equal(cf, ocf) and np.array_equal(rf, orf))
+        assert n == int(rf.sum()) and rows.tolist() == np.flatnonzero(rf.reshape(-1)).tolist()
+        assert orf.all()
+        H.assert_close(got, want, "all rows recomputed")
+
+
+def test_guard_equality_flags(oracle, H):
+    """Logits exactly on a bound must flag.  q = 8 e_1 and scale = 1/8 make the
+    logit equal to the key's first element exactly in fp32."""
+    S = 512
+    case = synth.make_case(B=1, Hq=4, Hkv=4, D=128, Smax=S, seed=320)
+    case["scale"] = 0.125
+    case["q"][:] = 0; case["q"][:, :, 0] = 8.0
+    case["k"][..., 0] = np.clip(case["k"][..., 0], -1.5, 1.5)      # logits in [-1.5, 1.5]
+    phi, lo, hi = 1.0, -3.0, 1.0
+    case["k"][0, 1, 300, 0] = 2.0            # x - phi == hi       -> flag, chunk 1 (chunk 256)
+    case["k"][0, 2, 10, 0] = -2.0            # x - phi == lo       -> flag, chunk 0
+    case["k"][0, 3, 511, 0] = 1.998046875    # one binary16 step inside hi -> no flag
+    ocf, orf, _ = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], phi, lo, hi, 256)
+    assert orf.reshape(-1).tolist() == [0, 1, 1, 0] and ocf[0, 1].tolist() == [0, 1] and ocf[0, 2].tolist() == [1, 0]
+    dc = H.DeviceCase(case, chunk=256)
+    got = dc.run("fd_decode_attn", phi=phi, bounds=(lo, hi))
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and rows.tolist() == [1, 2]
+    H.assert_close(got, exact(oracle, case), "equality")
+
+
+def test_invariance_to_phi_and_chunk(oracle, H):
+    """Eq. 3 and Eq. 4 on the GPU: moving phi inside the safe range or changing the
+    chunk size changes the output only by fp32 rounding noise."""
+    case = synth.make_case(B=1, Hq=4, Hkv=4, D=128, Smax=3000, seed=330, seq_lens=[2900])
+    ref = None
+    for chunk in (256, 512, 1024):
+        dc = H.DeviceCase(case, chunk=chunk)
+        for phi in (1.0, 3.0, 5.0):
+            got = dc.run("fd_decode_attn", phi=phi)
+            assert dc.flags()[2] == 0
+            ref = got if ref is None else ref
+            assert np.abs(got - ref).max() <= 2.5e-4      # <= a couple of fp16 ulps at |out| < 0.25
+    H.assert_close(ref, exact(oracle, case), "invariance")

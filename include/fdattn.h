@@ -75,8 +75,10 @@ typedef struct {
 typedef struct { float lo, hi; } fd_bounds;
 
 /* Caller-owned device scratch of at least fd_workspace_bytes(shape) bytes,
- * 256-byte aligned.  Contents before the call are irrelevant; after a call it
- * holds that call's partial results and flags (see fd_get_flags).             */
+ * 256-byte aligned.  After a call it holds that call's partial results and
+ * flags (see fd_get_flags, fd_get_partials).  fd_decode_attn and
+ * fd_decode_attn_gqa need the workspace prepared once by fd_workspace_init; the
+ * other calls accept arbitrary previous contents.                             */
 typedef struct { void *ptr; size_t bytes; } fd_workspace;
 
 /* Bytes of workspace the calls below need for this shape; 0 if the shape is
@@ -84,16 +86,34 @@ typedef struct { void *ptr; size_t bytes; } fd_workspace;
 size_t fd_workspace_bytes(const fd_shape *shape);
 
 /*
- * Asynchronized-softmax decode attention, one row at a time (Section 3).
- *   1. per (row, chunk): logits, range guard, sum e^{x-phi} and sum e^{x-phi} v
- *      with no maximum and no rescaling              (Eq. 4, inner sums)
- *   2. chunk flags -> row flags, list and count of flagged rows, on the device
- *   3. unflagged rows: out = (sum of numerators) / (sum of denominators)
- *                                                    (Eq. 4, outer sums)
- *   4. flagged rows only: recomputed by the synchronized partial softmax --
- *      per chunk (m, l, f.V), merged with e^{m_c - m} -- and written to out
- *                                                    (Eq. 2; "Recomputation")
- * Works for any head grouping (each query head is an independent row).
+ * Prepare a workspace for fd_decode_attn / fd_decode_attn_gqa: zeroes the
+ * per-row arrival tickets (one int32 per row) those calls use to elect the
+ * workgroup that finishes a row.  Enqueue once after allocating the workspace
+ * (or after changing the shape it is used with); every completed call leaves
+ * the tickets zero again, so steady-state calls need no re-initialisation.  A
+ * call that was aborted mid-flight (device reset, failed launch) needs a new one.
+ */
+fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream);
+
+/*
+ * Asynchronized-softmax decode attention, one row at a time (Section 3), in
+ * ONE kernel launch.  Per (row, chunk) workgroup:
+ *   1. logits, range guard, sum e^{x-phi} and sum e^{x-phi} v with no maximum
+ *      and no rescaling                               (Eq. 4, inner sums);
+ *   2. if the guard fired for this chunk, its partial softmax is recomputed at
+ *      once with the chunk's own maximum: (m, l, f.V)  (Eq. 2; "Recomputation");
+ *   3. the workgroup that completes a row last -- elected by one integer ticket
+ *      per row, the sums themselves use no atomics and run in fixed order --
+ *      forms the row: unflagged rows by the plain outer sums of Eq. 4, flagged
+ *      rows by the synchronized update of Eq. 2 over all partial results, each
+ *      rescaled from its own reference (phi, or the chunk maximum) to the row
+ *      maximum of those references.
+ * A flagged row is thus produced by the synchronized scheme, but only the
+ * partial vectors that left the bounds are re-read; the others already are
+ * valid partial-softmax results relative to phi.  fd_decode_attn_multikernel
+ * recomputes every chunk of a flagged row instead; both give the same result up
+ * to fp32 rounding.  Works for any head grouping (each query head is a row).
+ * Requires fd_workspace_init.  Fills chunk_flags and row_flags.
  */
 fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cache,
                          const void *v_cache, const int32_t *seq_lens, float phi,
@@ -105,10 +125,28 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
  * together so each K and V element is read from memory once per group.
  * Requires 2 <= n_q_heads / n_kv_heads <= 16.  (Grouping is not in the paper;
  * per query head the arithmetic is Eq. 4 unchanged.)  Flags are per query head.
+ * Requires fd_workspace_init.
  */
 fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,
                              const void *v_cache, const int32_t *seq_lens, float phi,
                              fd_bounds bounds, void *out, fd_workspace ws, void *stream);
+
+/*
+ * The same method as a chain of five small-step kernels with no atomics at all,
+ * following Section 3 to the letter:
+ *   1. per (row, chunk): Eq. 4 inner sums and the range guard;
+ *   2. chunk flags -> row flags, ascending list and count of flagged rows;
+ *   3. unflagged rows: Eq. 4 outer sums and the division;
+ *   4. flagged rows only: EVERY chunk of the row recomputed by the synchronized
+ *      partial softmax (m, l, f.V), work spread over the grid by (row, chunk);
+ *   5. flagged rows only: the synchronized update of Eq. 2, written to out.
+ * Needs no fd_workspace_init.  Five dependent launches cost about 12 us on an
+ * MI355X regardless of size, which is why fd_decode_attn fuses them.
+ * Fills chunk_flags, row_flags, n_flagged and flagged_rows.
+ */
+fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *seq_lens, float phi,
+                                     fd_bounds bounds, void *out, fd_workspace ws, void *stream);
 
 /*
  * The synchronized partial softmax (Eq. 2) applied to EVERY row: step 4 above
@@ -131,25 +169,36 @@ fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const voi
                                  fd_bounds bounds, fd_workspace ws, void *stream);
 
 /*
- * Device pointers into `ws` to the flags of the last fd_decode_attn /
- * fd_decode_attn_gqa call that used it (valid until the next call on `ws`):
+ * Device pointers into `ws` to the flags of the last decode call that used it
+ * (valid until the next call on `ws`):
  *   chunk_flags [batch*n_q_heads, ceil(max_seq/chunk)] uint8, 0 or 1
  *   row_flags   [batch*n_q_heads] uint8 = OR over the row's chunks
  *   n_flagged   [1] int32 = number of flagged rows
  *   flagged_rows[batch*n_q_heads] int32, the first *n_flagged entries are the
  *               flagged row indices in ascending order
- * Any output pointer may be NULL.  After fd_decode_attn_partial only
- * chunk_flags is meaningful.
+ * Any output pointer may be NULL.  chunk_flags is filled by every decode call
+ * that takes phi; row_flags by all of those except fd_decode_attn_partial;
+ * n_flagged and flagged_rows by fd_decode_attn_multikernel and by
+ * fd_list_flagged_rows only.
  */
 fd_status fd_get_flags(const fd_shape *shape, fd_workspace ws,
                        const uint8_t **chunk_flags, const uint8_t **row_flags,
                        const int32_t **n_flagged, const int32_t **flagged_rows);
 
 /*
+ * Enqueue the flag reduction alone: chunk_flags -> row_flags, flagged_rows and
+ * n_flagged (a single workgroup, prefix-sum compaction, no atomics).  For
+ * callers that want the list of recomputed rows after fd_decode_attn /
+ * fd_decode_attn_gqa, which do not need it themselves.
+ */
+fd_status fd_list_flagged_rows(const fd_shape *shape, const int32_t *seq_lens,
+                               fd_workspace ws, void *stream);
+
+/*
  * Device pointers into `ws` to the per-chunk partial results (D3 of Eq. 4):
  *   num [batch*n_q_heads, ceil(max_seq/chunk), head_dim] fp32 = sum e^{x-phi} v
  *   den [batch*n_q_heads, ceil(max_seq/chunk)]           fp32 = sum e^{x-phi}
- * Chunks without a valid key hold zeros.  Rows that were recomputed hold the
+ * Chunks without a valid key hold zeros.  Chunks that were recomputed hold the
  * synchronized scheme's (f.V, l) instead.
  */
 fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,

@@ -10,7 +10,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t num, den, mloc, chunk_flags, row_flags, list, count, total;
+    size_t num, den, mloc, chunk_flags, chunk_state, row_flags, list, count, ticket, total;
     long long rows, nc;
 };
 
@@ -37,9 +37,11 @@ fd_status plan(const fd_shape *sh, Layout *L)
     L->den = off;          off = align_up(off + slots * sizeof(float));
     L->mloc = off;         off = align_up(off + slots * sizeof(float));
     L->chunk_flags = off;  off = align_up(off + slots);
+    L->chunk_state = off;  off = align_up(off + slots * sizeof(int32_t));
     L->row_flags = off;    off = align_up(off + (size_t)rows);
     L->list = off;         off = align_up(off + (size_t)rows * sizeof(int32_t));
     L->count = off;        off = align_up(off + sizeof(int32_t));
+    L->ticket = off;       off = align_up(off + slots * sizeof(int32_t));
     L->total = off;
     L->rows = rows;
     L->nc = nc;
@@ -60,9 +62,11 @@ fd::WsView view(const Layout &L, fd_workspace ws)
     w.den = reinterpret_cast<float *>(base + L.den);
     w.mloc = reinterpret_cast<float *>(base + L.mloc);
     w.chunk_flags = reinterpret_cast<uint8_t *>(base + L.chunk_flags);
+    w.chunk_state = reinterpret_cast<int32_t *>(base + L.chunk_state);
     w.row_flags = reinterpret_cast<uint8_t *>(base + L.row_flags);
     w.list = reinterpret_cast<int32_t *>(base + L.list);
     w.count = reinterpret_cast<int32_t *>(base + L.count);
+    w.ticket = reinterpret_cast<int32_t *>(base + L.ticket);
     return w;
 }
 
@@ -104,13 +108,20 @@ fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
 
 #define FD_TRY(expr) do { if ((expr) != hipSuccess) return FD_ERR_HIP; } while (0)
 
-// Steps 2-4 shared by the per-row and the grouped entry points.
-fd_status finish_unified(const fd::Problem &p, hipStream_t s)
+// A problem description that carries only the shape and the workspace views.
+fd_status make_ws_problem(const fd_shape *sh, fd_workspace ws, fd::Problem *p)
 {
-    FD_TRY(fd::launch_flag_reduce(p, s));
-    FD_TRY(fd::launch_combine_unified(p, s));
-    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/true, s));
-    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/true, s));
+    Layout L;
+    fd_status st = plan(sh, &L);
+    if (st != FD_OK) return st;
+    st = check_ws(L, ws);
+    if (st != FD_OK) return st;
+    *p = fd::Problem{};
+    p->ws = view(L, ws);
+    p->B = sh->batch; p->Hq = sh->n_q_heads; p->Hkv = sh->n_kv_heads;
+    p->G = sh->n_q_heads / sh->n_kv_heads;
+    p->Smax = sh->max_seq; p->C = sh->chunk; p->nc = (int)L.nc; p->rows = (int)L.rows;
+    p->scale = sh->scale;
     return FD_OK;
 }
 
@@ -138,6 +149,15 @@ fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const voi
     return FD_OK;
 }
 
+fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_ws_problem(shape, ws, &p);
+    if (st != FD_OK) return st;
+    FD_TRY(fd::launch_clear_tickets(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
 fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cache,
                          const void *v_cache, const int32_t *seq_lens, float phi,
                          fd_bounds bounds, void *out, fd_workspace ws, void *stream)
@@ -148,9 +168,8 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
     st = set_guard(&p, phi, bounds);
     if (st != FD_OK) return st;
     if (p.rows == 0) return FD_OK;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    FD_TRY(fd::launch_partial_unified(p, s));
-    return finish_unified(p, s);
+    FD_TRY(fd::launch_decode_fused(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
 }
 
 fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,
@@ -164,9 +183,38 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
     if (st != FD_OK) return st;
     if (p.G < 2 || p.G > 16) return FD_ERR_UNSUPPORTED;
     if (p.rows == 0) return FD_OK;
+    FD_TRY(fd::launch_decode_fused_gqa(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
+fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *seq_lens, float phi,
+                                     fd_bounds bounds, void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    FD_TRY(fd::launch_partial_unified_gqa(p, s));
-    return finish_unified(p, s);
+    FD_TRY(fd::launch_partial_unified(p, s));
+    FD_TRY(fd::launch_flag_reduce(p, s));
+    FD_TRY(fd::launch_combine_unified(p, s));
+    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/true, s));
+    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/true, s));
+    return FD_OK;
+}
+
+fd_status fd_list_flagged_rows(const fd_shape *shape, const int32_t *seq_lens, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_ws_problem(shape, ws, &p);
+    if (st != FD_OK) return st;
+    if (!seq_lens) return FD_ERR_NULL;
+    p.seq_lens = seq_lens;
+    FD_TRY(fd::launch_flag_reduce(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
 }
 
 fd_status fd_decode_attn_sync(const fd_shape *shape, const void *q, const void *k_cache,

@@ -1,0 +1,374 @@
+// Device code shared by the chunk kernels: the per-(row, chunk) body of the VALU
+// path and the row epilogue (outer sums / synchronized merge).
+//
+// Lane layout of the VALU path.  A K or V row is 256 bytes = 16 segments of 16
+// bytes; lane l of a wavefront owns segment l%16 of key (l/16) within a group of
+// 4 consecutive keys, so one wavefront load instruction reads 1 KiB of contiguous
+// cache memory with 128-bit loads.  The four wavefronts of a workgroup interleave
+// groups, i.e. the workgroup walks the chunk front to back 4 KiB at a time.  The
+// 16 lanes of a key reduce their 8-element partial dot products with DPP row
+// operations (a DPP row is exactly 16 lanes), after which every one of the 16
+// lanes holds the key's logit and scales its own 8 elements of the V row.
+// K and V are read exactly once and never reused, so they are loaded with
+// non-temporal loads straight into registers; LDS only carries the final
+// cross-wavefront reduction.
+#pragma once
+
+#include "fd_internal.h"
+
+namespace fd {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+
+// 128-bit streaming load: the data is used once, keep it from displacing other lines.
+__device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+// fp32 dot product of 8 fp16 pairs; every product is exact in fp32.
+__device__ __forceinline__ float dot8(const u32x4 &a, const u32x4 &b)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const half2_t x = as_h2(a[i]), y = as_h2(b[i]);
+        acc = __builtin_fmaf((float)x.x, (float)y.x, acc);
+        acc = __builtin_fmaf((float)x.y, (float)y.y, acc);
+    }
+    return acc;
+}
+
+// acc[0..7] += p * v[0..7]
+__device__ __forceinline__ void axpy8(float (&acc)[8], float p, const u32x4 &v)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const half2_t x = as_h2(v[i]);
+        acc[2 * i]     = __builtin_fmaf(p, (float)x.x, acc[2 * i]);
+        acc[2 * i + 1] = __builtin_fmaf(p, (float)x.y, acc[2 * i + 1]);
+    }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_swap(float x)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane ends with the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_swap<0xB1>(x);   // quad_perm [1,0,3,2]  : lane ^ 1
+    x += dpp_swap<0x4E>(x);   // quad_perm [2,3,0,1]  : lane ^ 2
+    x += dpp_swap<0x141>(x);  // row_half_mirror      : other quad of the 8
+    x += dpp_swap<0x140>(x);  // row_mirror           : other half of the 16
+    return x;
+}
+
+// Device-coherent accesses for results that another workgroup of the SAME launch
+// reads (the per-chunk partial results and the per-row ticket).  Each XCD has its
+// own L2, so such data is written through and read past the L2 ("agent scope"
+// relaxed atomics); ordinary cached accesses would need an L2 write-back fence per
+// workgroup, which costs about a microsecond each and serializes per XCD.
+template <typename T>
+__device__ __forceinline__ void store_coherent(T *p, T v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ T load_coherent(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Wait until this thread's earlier stores are performed (vector memory counter at
+// zero); with write-through stores this is the release half of the hand-over.
+__device__ __forceinline__ void wait_stores_performed()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+__device__ __forceinline__ uint16_t to_half_bits(float x)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)x);   // round to nearest even
+}
+
+// LDS of one workgroup of NW wavefronts.  XN = number of logits kept for the
+// synchronized scheme.
+template <int NW, int XN>
+struct ChunkLds {
+    float acc[NW * 4][kHeadDim];   // [wave*4 + key-in-group][element]; reused by the row epilogue
+    float x[XN];
+    float den[NW * 4];
+    float mx[NW];
+    int   flag[NW];
+    int   last;
+};
+
+// One (row, chunk) on the VALU path, by a workgroup of NW wavefronts.
+//   SYNC == false : unified scaling factor phi -- Eq. 4 inner sums and the range
+//                   guard of Section 3 "Recomputation".  Writes num, den,
+//                   chunk_flags and mloc = phi (the reference the sums are scaled by).
+//   SYNC == true  : the chunk's part of the synchronized partial softmax, Eq. 2:
+//                   m = max x, l = sum e^{x-m}, f.V = sum e^{x-m} v.  Writes num,
+//                   den, mloc = m and leaves chunk_flags alone.
+// UP = groups of 4 keys per wavefront per pipeline stage.
+// Returns (uniformly over the workgroup) whether the guard fired (false for SYNC).
+template <int C, int NW, int UP, bool SYNC, int XN>
+__device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds)
+{
+    static_assert(!SYNC || XN >= C, "the synchronized scheme keeps the chunk's logits in LDS");
+    constexpr int NG = C / (4 * NW);           // groups of 4 keys each wavefront handles
+    static_assert(NG >= 1 && NG % UP == 0, "chunk, wavefront count and stage depth must divide");
+    constexpr int NBLK = NG / UP;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int seg = lane & 15, sub = lane >> 4;
+
+    const int b = row / p.Hq;
+    const int hq = row - b * p.Hq;
+    const int hkv = hq / p.G;
+    const int S = valid_len(p, b);
+    const int start = c * C;
+    const int nvalid = min(C, S - start);      // <= 0: no valid key in this chunk
+    const size_t slot = (size_t)row * p.nc + c;
+
+    if (nvalid <= 0) {                         // empty chunk: zero partials, no flag
+        if (tid < kHeadDim) p.ws.num[slot * kHeadDim + tid] = 0.f;
+        if (tid == 0) {
+            p.ws.den[slot] = 0.f;
+            p.ws.mloc[slot] = SYNC ? -INFINITY : p.phi;
+            if (!SYNC) { p.ws.chunk_flags[slot] = 0; p.ws.chunk_state[slot] = 0; }
+        }
+        return false;
+    }
+
+    const u32x4 qv = reinterpret_cast<const u32x4 *>(p.q + (size_t)row * kHeadDim)[seg];
+    const size_t kv_off = (((size_t)b * p.Hkv + hkv) * p.Smax + start) * kHeadDim;
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + seg;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + seg;
+    const int last = nvalid - 1;
+    // key handled by this lane in group g of the chunk: the NW wavefronts interleave
+    auto key_of = [&](int g) { return (g * NW + wave) * 4 + sub; };
+    // blocks (of UP groups per wavefront) that hold at least one valid key
+    const int nblk = min(NBLK, (nvalid + UP * NW * 4 - 1) / (UP * NW * 4));
+
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    float mc = p.phi;
+
+    if constexpr (!SYNC) {
+        // Software pipeline over blocks of UP groups: the loads of block i+1 are in
+        // flight while block i is reduced.  Keys past the valid length re-read the
+        // last valid key (always in bounds, never padding) and get weight zero.
+        const float nphi = -p.phi, lo = p.lo, hi = p.hi, scale = p.scale;
+        bool bad = false;
+        auto issue = [&](int blk, u32x4 (&kk)[UP], u32x4 (&vv)[UP]) {
+#pragma unroll
+            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)min(key_of(blk * UP + u), last) * 16);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)min(key_of(blk * UP + u), last) * 16);
+        };
+        auto reduce = [&](int blk, const u32x4 (&kk)[UP], const u32x4 (&vv)[UP]) {
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const bool valid = key_of(blk * UP + u) <= last;
+                const float x = row16_sum(dot8(qv, kk[u])) * scale;
+                const float d = x + nphi;                       // x - phi
+                bad |= valid & !((d > lo) & (d < hi));          // equality and NaN flag
+                float e = __builtin_amdgcn_exp2f(d * kLog2e);   // e^{x - phi}
+                e = valid ? e : 0.f;
+                den += e;
+                axpy8(acc, e, vv[u]);
+            }
+        };
+        // The steady-state loop issues unconditionally (a load inside a branch
+        // would force a full wait at the join); the last one or two blocks are peeled.
+        u32x4 kA[UP], vA[UP], kB[UP], vB[UP];
+        issue(0, kA, vA);
+        int blk = 0;
+#pragma unroll 1
+        for (; blk + 2 < nblk; blk += 2) {
+            issue(blk + 1, kB, vB);
+            reduce(blk, kA, vA);
+            issue(blk + 2, kA, vA);
+            reduce(blk + 1, kB, vB);
+        }
+        if (blk + 2 == nblk) {
+            issue(blk + 1, kB, vB);
+            reduce(blk, kA, vA);
+            reduce(blk + 1, kB, vB);
+        } else {
+            reduce(blk, kA, vA);
+        }
+        const unsigned long long any_bad = __ballot(bad);
+        if (lane == 0) lds.flag[wave] = any_bad != 0ull;
+    } else {
+        // Pass 1: logits of the whole chunk into LDS, and their maximum.
+        float m = -INFINITY;
+        const float scale = p.scale;
+#pragma unroll 1
+        for (int blk = 0; blk < nblk; ++blk) {
+            u32x4 kk[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)min(key_of(blk * UP + u), last) * 16);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const int kidx = key_of(blk * UP + u);
+                float x = row16_sum(dot8(qv, kk[u])) * scale;
+                x = kidx <= last ? x : -INFINITY;
+                if (seg == 0) lds.x[kidx] = x;
+                m = fmaxf(m, x);
+            }
+        }
+        // chunk maximum: over the 4 keys of the lane's column, then the wavefronts
+        m = fmaxf(m, __shfl_xor(m, 16));
+        m = fmaxf(m, __shfl_xor(m, 32));
+        if (lane == 0) lds.mx[wave] = m;
+        __syncthreads();
+        mc = lds.mx[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) mc = fmaxf(mc, lds.mx[w]);
+        // Pass 2: e^{x - m} and the V products.
+#pragma unroll 1
+        for (int blk = 0; blk < nblk; ++blk) {
+            u32x4 vv[UP];
+#pragma unroll
+            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)min(key_of(blk * UP + u), last) * 16);
+#pragma unroll
+            for (int u = 0; u < UP; ++u) {
+                const float e = __builtin_amdgcn_exp2f((lds.x[key_of(blk * UP + u)] - mc) * kLog2e);   // 0 for padding
+                den += e;
+                axpy8(acc, e, vv[u]);
+            }
+        }
+    }
+
+    // Workgroup reduction: NW*4 partial vectors (NW wavefronts x 4 keys per group).
+    float4 *dst = reinterpret_cast<float4 *>(&lds.acc[wave * 4 + sub][seg * 8]);
+    dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    if (seg == 0) lds.den[wave * 4 + sub] = den;
+    __syncthreads();
+    bool flagged = false;
+    if constexpr (!SYNC) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) flagged |= lds.flag[w] != 0;
+    }
+    if (tid < kHeadDim) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NW * 4; ++i) s += lds.acc[i][tid];
+        store_coherent(&p.ws.num[slot * kHeadDim + tid], s);
+    } else if (tid == kHeadDim) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < NW * 4; ++i) s += lds.den[i];
+        store_coherent(&p.ws.den[slot], s);
+        store_coherent(&p.ws.mloc[slot], mc);
+        if (!SYNC) {
+            store_coherent(&p.ws.chunk_state[slot], flagged ? 1 : 0);
+            p.ws.chunk_flags[slot] = flagged ? 1 : 0;      // host-visible copy, read after the launch
+        }
+    }
+    return flagged;
+}
+
+// Row epilogue, run by the one workgroup that owns the row's output (its first 256
+// threads do the arithmetic): the synchronized update of Eq. 2 over the row's
+// partial results, each scaled by its own reference r_c -- phi for chunks summed
+// with the unified factor, the chunk maximum for recomputed ones:
+//     m = max_c r_c,   out = sum_c e^{r_c-m} num_c / sum_c e^{r_c-m} den_c.
+// For a row without flags every r_c is phi, every factor is exactly 1 and the
+// expression IS the plain outer sum of Eq. 4 (same bits), so one code path serves
+// both.  Sums run in chunk order (even chunks, odd chunks, then the two halves): no
+// atomics on data, same bits on every run.  The partial results come from other
+// workgroups of the same launch, hence the coherent loads; these pass the caches,
+// so they are issued in batches before anything waits on them.
+// `scratch` is >= 256 floats of LDS, `red` >= NW floats.
+template <int NW>
+__device__ __forceinline__ void row_epilogue(const Problem &p, int row, int nb, float *scratch, float *red)
+{
+    constexpr int UB = 16;                      // chunks per thread and batch
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int half = (tid >> 7) & 1, t = tid & (kHeadDim - 1);
+    const bool worker = tid < 256;
+    const size_t r0 = (size_t)row * p.nc;
+    const float *num = p.ws.num + r0 * kHeadDim + t;
+    const float *den = p.ws.den + r0;
+    const float *ref = p.ws.mloc + r0;
+
+    // row maximum of the references and the row flag: one strided load per chunk
+    float m = -INFINITY;
+    int f = 0;
+    for (int c = tid; c < nb; c += NW * 64) {
+        m = fmaxf(m, load_coherent(&ref[c]));
+        f |= load_coherent(&p.ws.chunk_state[r0 + c]);
+    }
+    // first batch of partial results, issued before anything above is waited for
+    float nv[UB], rv[UB], dv[UB];
+    auto issue = [&](int c0) {
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            const int c = c0 + 2 * i + half;
+            const bool on = worker && c < nb;
+            nv[i] = on ? load_coherent(&num[(size_t)c * kHeadDim]) : 0.f;
+            rv[i] = on ? load_coherent(&ref[c]) : -INFINITY;
+            dv[i] = on ? load_coherent(&den[c]) : 0.f;
+        }
+    };
+    issue(0);
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red[wave] = m;
+    const int rf = __syncthreads_or(f);
+    m = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
+
+    float s = 0.f, l = 0.f;
+    for (int c0 = 0; c0 < nb; c0 += 2 * UB) {
+        if (c0) issue(c0);
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            const float a = __builtin_amdgcn_exp2f((rv[i] - m) * kLog2e);   // exactly 1 when r_c == m
+            s = __builtin_fmaf(a, nv[i], s);
+            l = __builtin_fmaf(a, dv[i], l);
+        }
+    }
+    if (worker && half) { scratch[t] = s; scratch[kHeadDim + t] = l; }
+    __syncthreads();
+    if (worker && !half) {
+        s += scratch[t];
+        l += scratch[kHeadDim + t];
+        p.out[(size_t)row * kHeadDim + t] = nb > 0 ? to_half_bits(s / l) : (uint16_t)0;
+    }
+    if (tid == 0) p.ws.row_flags[row] = rf ? 1 : 0;
+}
+
+// Elects the workgroup that completes a row: a radix-8 tree of arrival counters
+// over the row's nb chunks.  Same-address device-scope atomics complete one after
+// another (about 0.13 us each on MI355X), so a flat counter costs nb of them on the
+// critical path when the workgroups of a row finish together; the tree costs at
+// most 8 per level plus one memory round trip per level.  Called by one thread after the workgroup's results are performed.
+// Returns true for exactly one caller per row, after every other chunk arrived.
+// Counters are zero before and after (the last arrival at a node resets it).
+__device__ __forceinline__ bool arrive_and_elect(const Problem &p, int row, int c, int nb)
+{
+    constexpr int LR = 3, R = 1 << LR;
+    int32_t *node = p.ws.ticket + (size_t)row * p.nc;
+    int idx = c, n = nb;
+    while (n > 1) {
+        const int parent = idx >> LR;
+        const int children = min(R, n - (parent << LR));
+        const int t = __hip_atomic_fetch_add(&node[parent], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (t != children - 1) return false;
+        store_coherent(&node[parent], 0);
+        n = (n + R - 1) >> LR;
+        node += n;
+        idx = parent;
+    }
+    return true;
+}
+
+}  // namespace fd

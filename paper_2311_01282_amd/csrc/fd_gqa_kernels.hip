@@ -1,6 +1,247 @@
-// Grouped-query chunk kernel (MFMA path) -- placeholder until the kernel lands.
-#include "fd_internal.h"
+// Grouped-query chunk kernel (MFMA path): the G <= 16 query heads that share one
+// KV head are processed together, so every K and V element is read from HBM once
+// per group instead of once per query head.  With G = 8 the work is 8 flop per KV
+// byte, more than the vector ALUs sustain at HBM rate once fp16->fp32 conversions
+// are counted, hence the matrix cores:
+//
+//   scores   S^T[key][head] = sum_d K[key][d] Q[head][d]
+//            v_mfma_f32_16x16x32_f16: A = a 16-key block of K, B = Q padded to 16
+//            heads (zero rows), 4 instructions per block (d = 4 x 32).
+//   weights  P = e^{s S^T - phi} in fp32, in place in the accumulator layout
+//            (lane (head, g) holds keys 4g..4g+3 of the block) -- Eq. 4, no maximum.
+//            fp16 cannot hold e^{x-phi} over the admissible range of x - phi, so
+//            the second product stays in fp32:
+//   P.V      out[head][d] += sum_key P[head][key] V[key][d]
+//            v_mfma_f32_16x16x4_f32: A = P (one fp32 per lane: exactly the layout the
+//            score tile leaves behind), B = V converted to fp32.  Lane (n, g) loads
+//            the 16 bytes d = 8n..8n+7 of key 4g+r and feeds element e of them to
+//            accumulator tile e, so V needs no transpose either: 32 instructions
+//            per 16-key block.
+//
+// K reaches the A layout through a per-wavefront LDS tile (coalesced 1 KiB global
+// loads in, 16-byte reads out, XOR-swizzled so both directions are bank-conflict
+// free).  One workgroup = 4 wavefronts = one (sequence, KV head, chunk); the
+// wavefronts interleave 16-key blocks.  The rest of the method -- guard, on-the-spot
+// recomputation of a flagged (head, chunk) with the synchronized scheme, election of
+// the workgroup that completes the group, row epilogue -- is shared with the per-row
+// kernels (fd_chunk.h).
+#include "fd_chunk.h"
 
 namespace fd {
-hipError_t launch_partial_unified_gqa(const Problem &, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kGqaThreads = 256;
+constexpr int kTileFloats = 4 * 16 * kHeadDim;   // [wave][head][d] reduction tile, 32 KiB
+
+struct GqaLds {
+    // K staging (4 wavefronts x 4 KiB) during the main loop, then the reduction tile,
+    // then (rarely) the per-row recomputation's workspace: never live together.
+    alignas(16) float tile[kTileFloats];
+    float den[4][64];
+    unsigned long long bad[4];
+    float red[4];
+    int last;
+};
+
+__device__ __forceinline__ void cvt8(const u32x4 &v, float (&o)[8])
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const half2_t h = as_h2(v[i]);
+        o[2 * i] = (float)h.x;
+        o[2 * i + 1] = (float)h.y;
+    }
+}
+
+template <int C>
+__global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Problem p)
+{
+    static_assert(sizeof(ChunkLds<4, C>) <= sizeof(float) * kTileFloats, "recompute workspace must fit the tile");
+    __shared__ GqaLds lds;
+    constexpr int NBLK = C / 16;               // 16-key blocks in the chunk
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, g = lane >> 4;    // n: head (scores) / 16-byte segment (loads); g: lane group
+    const int G = p.G;
+
+    // All chunks of a KV-head group go to the same XCD (see decode_fused_kernel).
+    const int groups = p.B * p.Hkv;
+    const int j = blockIdx.x >> 3;
+    const int gi = (blockIdx.x & 7) + 8 * (j / p.nc), c = j % p.nc;
+    if (gi >= groups) return;
+    const int b = gi / p.Hkv;
+    const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group
+    const int S = valid_len(p, b);
+    const int nb = (S + C - 1) / C;
+    const int start = c * C;
+    const int nvalid = min(C, S - start);
+
+    if (nvalid <= 0) {                         // padding chunk: zero partials, no flag
+        for (int i = tid; i < G * kHeadDim; i += kGqaThreads)
+            p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + (i & (kHeadDim - 1))] = 0.f;
+        if (tid < G) {
+            const size_t slot = (size_t)(row0 + tid) * p.nc + c;
+            p.ws.den[slot] = 0.f; p.ws.mloc[slot] = p.phi;
+            p.ws.chunk_flags[slot] = 0; p.ws.chunk_state[slot] = 0;
+            if (nb == 0 && c == 0) p.ws.row_flags[row0 + tid] = 0;
+        }
+        if (nb == 0 && c == 0)                 // empty sequence: nobody else owns these rows
+            for (int i = tid; i < G * kHeadDim; i += kGqaThreads) p.out[(size_t)row0 * kHeadDim + i] = 0;
+        return;
+    }
+
+    // Q as the B operand: lane (n, g) holds d = 32kb + 8g .. +7 of head n; heads >= G are zero rows.
+    f16x8 qb[4];
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+        u32x4 t = {0u, 0u, 0u, 0u};
+        if (n < G) t = *reinterpret_cast<const u32x4 *>(p.q + (size_t)(row0 + n) * kHeadDim + 32 * kb + 8 * g);
+        qb[kb] = __builtin_bit_cast(f16x8, t);
+    }
+
+    const size_t kv_off = ((size_t)gi * p.Smax + start) * kHeadDim;
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + n;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + n;
+    const int last = nvalid - 1;
+    const float nphi = -p.phi, lo = p.lo, hi = p.hi, scale = p.scale;
+    u32x4 *kst = reinterpret_cast<u32x4 *>(lds.tile) + wave * 256;     // this wavefront's 16 x 16 slots
+
+    f32x4 acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float den = 0.f;
+    bool bad = false;
+    const bool head_on = n < G;
+
+#pragma unroll 1
+    for (int blk = wave; blk < NBLK; blk += 4) {
+        const int k0 = blk * 16;
+        if (k0 >= nvalid) break;               // uniform per wavefront: rest is padding
+        // Keys past the valid length re-read the last valid key and get weight zero.
+        u32x4 kk[4], vv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + (size_t)min(k0 + 4 * i + g, last) * 16);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + (size_t)min(k0 + 4 * g + r, last) * 16);
+
+        // K block -> LDS row (4i + g), 16-byte slot n ^ row; then out in the A layout:
+        // lane (n, g) takes slot (4kb + g) ^ n of row n.
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 4 * i + g;
+            kst[r * 16 + (n ^ r)] = kk[i];
+        }
+        f32x4 sc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            const f16x8 ka = __builtin_bit_cast(f16x8, kst[n * 16 + ((4 * kb + g) ^ n)]);
+            sc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kb], sc, 0, 0, 0);
+        }
+        // sc[r] = <q_head n, k_key>, key = k0 + 4g + r.  Guard, then e^{x - phi}.
+        float pw[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool valid = k0 + 4 * g + r <= last;
+            const float d = sc[r] * scale + nphi;
+            bad |= valid & head_on & !((d > lo) & (d < hi));
+            const float e = __builtin_amdgcn_exp2f(d * kLog2e);
+            pw[r] = valid ? e : 0.f;
+            den += pw[r];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float ve[8];
+            cvt8(vv[r], ve);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pw[r], ve[e], acc[e], 0, 0, 0);
+        }
+    }
+
+    // ---- workgroup reduction and publication of the G rows' partial results ----
+    const unsigned long long bad_mask = __ballot(bad);
+    __syncthreads();                           // every wavefront is done with its K staging
+    // acc[e][r] is (head 4g + r, d = 8n + e) of this wavefront's partial tile.
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int h = 4 * g + r;
+        if (h < G) {
+            float4 *dst = reinterpret_cast<float4 *>(&lds.tile[(wave * 16 + h) * kHeadDim + 8 * n]);
+            dst[0] = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+            dst[1] = make_float4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
+        }
+    }
+    lds.den[wave][lane] = den;
+    if (lane == 0) lds.bad[wave] = bad_mask;
+    __syncthreads();
+    for (int i = tid; i < G * kHeadDim; i += kGqaThreads) {
+        const float s = lds.tile[i] + lds.tile[16 * kHeadDim + i] + lds.tile[32 * kHeadDim + i] + lds.tile[48 * kHeadDim + i];
+        store_coherent(&p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + (i & (kHeadDim - 1))], s);
+    }
+    const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
+    // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
+    const unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
+    if (tid < G) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) s += lds.den[w][tid + 16 * q4];
+        const size_t slot = (size_t)(row0 + tid) * p.nc + c;
+        const int f = (flagged_heads >> tid) & 1;
+        store_coherent(&p.ws.den[slot], s);
+        store_coherent(&p.ws.mloc[slot], p.phi);
+        store_coherent(&p.ws.chunk_state[slot], f);
+        p.ws.chunk_flags[slot] = (uint8_t)f;
+    }
+
+    // Section 3 "Recomputation": a (head, chunk) whose guard fired is redone with the
+    // synchronized scheme on the per-row path (rare; re-reads this chunk only).
+    if (flagged_heads) {
+        wait_stores_performed();               // the stores above must not overtake the rewrite
+        for (int h = 0; h < G; ++h) {
+            if (!((flagged_heads >> h) & 1)) continue;
+            __syncthreads();
+            chunk_body<C, 4, (C / 16 < 8 ? C / 16 : 8), true>(p, row0 + h, c, *reinterpret_cast<ChunkLds<4, C> *>(lds.tile));
+        }
+    }
+
+    // Publish, arrive, and let the last arrival of the group finish its G rows.
+    wait_stores_performed();
+    __syncthreads();
+    if (tid == 0) lds.last = arrive_and_elect(p, row0, c, nb);
+    __syncthreads();
+    if (!lds.last) return;
+    for (int h = 0; h < G; ++h) {
+        row_epilogue<4>(p, row0 + h, nb, lds.tile, lds.red);
+        __syncthreads();
+    }
+}
+
+template <int C> struct GqaLauncher {
+    static hipError_t run(const Problem &p, hipStream_t s)
+    {
+        const long long groups = (long long)p.B * p.Hkv;
+        const unsigned grid = (unsigned)(8ll * ((groups + 7) / 8) * p.nc);
+        if (grid == 0) return hipSuccess;
+        return launch(decode_fused_gqa_kernel<C>, dim3(grid), dim3(kGqaThreads), s, p);
+    }
+};
+
+}  // namespace
+
+hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s)
+{
+    switch (p.C) {
+        case 64:   return GqaLauncher<64>::run(p, s);
+        case 128:  return GqaLauncher<128>::run(p, s);
+        case 256:  return GqaLauncher<256>::run(p, s);
+        case 512:  return GqaLauncher<512>::run(p, s);
+        case 1024: return GqaLauncher<1024>::run(p, s);
+        default:   return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace fd

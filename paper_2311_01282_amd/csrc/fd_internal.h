@@ -9,7 +9,6 @@
 namespace fd {
 
 constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
-constexpr int kThreads = 256;      // 4 wavefronts per workgroup in the chunk kernels
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Views into the caller's workspace.
@@ -18,9 +17,11 @@ struct WsView {
     float   *den;          // [rows, nc]       sum e^{x-phi}     (or l)
     float   *mloc;         // [rows, nc]       chunk maximum m (synchronized scheme only)
     uint8_t *chunk_flags;  // [rows, nc]
+    int32_t *chunk_state;  // [rows, nc]  the same flags as words, handed between workgroups of one launch
     uint8_t *row_flags;    // [rows]
     int32_t *list;         // [rows]  flagged rows, ascending
     int32_t *count;        // [1]     number of flagged rows
+    int32_t *ticket;       // [rows, nc]  arrival counters (a small tree per row) of the fused kernels; zero between calls
 };
 
 struct Problem {
@@ -50,14 +51,16 @@ inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStr
 }
 
 // fd_row_kernels.hip : one query head per workgroup (VALU path)
+hipError_t launch_decode_fused(const Problem &p, hipStream_t s);
 hipError_t launch_partial_unified(const Problem &p, hipStream_t s);
 hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s);
 // fd_reduce_kernels.hip : flag reduction and the two combines
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s);
 hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
 hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
+hipError_t launch_clear_tickets(const Problem &p, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
-hipError_t launch_partial_unified_gqa(const Problem &p, hipStream_t s);
+hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s);
 // fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling
 hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, unsigned *sink, hipStream_t s);
 

@@ -9,17 +9,17 @@ namespace {
 
 constexpr int kTile = 65536;   // bytes of each buffer per workgroup
 
-__global__ __launch_bounds__(kThreads) void stream_read_kernel(const uint4 *a, const uint4 *b, unsigned *sink)
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *a, const uint4 *b, unsigned *sink)
 {
     const size_t base = (size_t)blockIdx.x * (kTile / 16) + threadIdx.x;
     uint4 acc = make_uint4(0, 0, 0, 0);
 #pragma unroll 1
-    for (int i = 0; i < kTile / 16 / kThreads; i += 8) {
+    for (int i = 0; i < kTile / 16 / 256; i += 8) {
         uint4 x[8], y[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = a[base + (size_t)(i + u) * kThreads];
+        for (int u = 0; u < 8; ++u) x[u] = a[base + (size_t)(i + u) * 256];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) y[u] = b[base + (size_t)(i + u) * kThreads];
+        for (int u = 0; u < 8; ++u) y[u] = b[base + (size_t)(i + u) * 256];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             acc.x ^= x[u].x ^ y[u].x; acc.y ^= x[u].y ^ y[u].y;
@@ -36,7 +36,7 @@ hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, u
 {
     const size_t tiles = bytes_each / kTile;
     if (tiles == 0) return hipSuccess;
-    return launch(stream_read_kernel, dim3((unsigned)tiles), dim3(kThreads), s,
+    return launch(stream_read_kernel, dim3((unsigned)tiles), dim3(256), s,
                   static_cast<const uint4 *>(a), static_cast<const uint4 *>(b), sink);
 }
 

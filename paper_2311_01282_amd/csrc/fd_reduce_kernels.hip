@@ -1,14 +1,15 @@
-// Small kernels that follow the chunk kernels: flag reduction, the outer sums of
+// Small kernels of the multi-kernel chain: flag reduction, the outer sums of
 // Eq. 4 (atomic-free: one workgroup owns one output row), and the synchronized
-// merge of Eq. 2 for recomputed rows.
-#include "fd_internal.h"
+// merge of Eq. 2 for recomputed rows.  Plus the ticket clear of fd_workspace_init.
+#include "fd_chunk.h"
 
 namespace fd {
 namespace {
 
-__device__ __forceinline__ uint16_t to_half_bits(float x)
+__global__ __launch_bounds__(256) void clear_tickets_kernel(int32_t *ticket, int n)
 {
-    return __builtin_bit_cast(uint16_t, (_Float16)x);   // round to nearest even
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) ticket[i] = 0;
 }
 
 // Chunk flags -> row flags, ascending list of flagged rows, their count.
@@ -92,6 +93,13 @@ __global__ __launch_bounds__(kHeadDim) void combine_sync_kernel(const Problem p,
 }
 
 }  // namespace
+
+hipError_t launch_clear_tickets(const Problem &p, hipStream_t s)
+{
+    const int n = p.rows * p.nc;
+    if (n == 0) return hipSuccess;
+    return launch(clear_tickets_kernel, dim3((n + 255) / 256), dim3(256), s, p.ws.ticket, n);
+}
 
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s)
 {

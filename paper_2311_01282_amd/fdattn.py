@@ -51,7 +51,7 @@ _lib.fd_workspace_bytes.restype = ctypes.c_size_t
 _lib.fd_workspace_bytes.argtypes = [_sp]
 _lib.fd_status_str.restype = ctypes.c_char_p
 _lib.fd_status_str.argtypes = [ctypes.c_int]
-for _name in ("fd_decode_attn", "fd_decode_attn_gqa"):
+for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel"):
     getattr(_lib, _name).restype = ctypes.c_int
     getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
 _lib.fd_decode_attn_sync.restype = ctypes.c_int
@@ -63,10 +63,15 @@ _lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
 _lib.fd_get_partials.restype = ctypes.c_int
 _lib.fd_get_partials.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 2
 
+_lib.fd_workspace_init.restype = ctypes.c_int
+_lib.fd_workspace_init.argtypes = [_sp, Workspace, _vp]
+_lib.fd_list_flagged_rows.restype = ctypes.c_int
+_lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
 _lib.fd_probe_stream_read.restype = ctypes.c_int
 _lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 
-EXPORTS = ("fd_workspace_bytes", "fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_sync",
+EXPORTS = ("fd_workspace_bytes", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+           "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
 
@@ -97,6 +102,19 @@ def fd_decode_attn(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_pt
 def fd_decode_attn_gqa(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
     _check(_lib.fd_decode_attn_gqa(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
                                    Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_multikernel(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_multikernel(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                                           Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_workspace_init(shape, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_workspace_init(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_list_flagged_rows(shape, seq_lens, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_list_flagged_rows(ctypes.byref(shape), seq_lens, Workspace(ws_ptr, ws_bytes), stream))
 
 
 def fd_decode_attn_sync(shape, q, k_cache, v_cache, seq_lens, out, ws_ptr, ws_bytes, stream=0):

@@ -85,17 +85,18 @@ def make_config(name, layer=0, **overrides):
     return case
 
 
-def plant_keys(case, n_rows, gamma, seed):
+def plant_keys(case, n_rows, gamma, seed, allow_shared_kv=False):
     """Overwrite one key in each of ``n_rows`` distinct (b, hq) rows with
     ``gamma * q / ||q||`` (float16), at a seeded position among the valid keys.
 
-    Only meaningful when every query head has its own KV head (Hq == Hkv); with
-    shared KV heads the planted key would also enter the other rows of the
-    group.  Returns the list of (b, hq, position).  The V row at that position
-    keeps its random value.
+    With shared KV heads (Hq != Hkv) the planted key also enters the other rows
+    of the group (with a logit of about gamma * N(0,1) / sqrt(D)); this must be
+    asked for with ``allow_shared_kv``.  Returns the list of (b, hq, position).
+    The V row at that position keeps its random value.
     """
-    if case["Hq"] != case["Hkv"]:
-        raise ValueError("plant_keys needs Hq == Hkv")
+    if case["Hq"] != case["Hkv"] and not allow_shared_kv:
+        raise ValueError("plant_keys needs Hq == Hkv unless allow_shared_kv is set")
+    G = case["Hq"] // case["Hkv"]
     rng = np.random.default_rng(seed)
     rows = case["B"] * case["Hq"]
     picked = rng.choice(rows, size=n_rows, replace=False)
@@ -107,6 +108,6 @@ def plant_keys(case, n_rows, gamma, seed):
             continue
         pos = int(rng.integers(0, n))
         qv = case["q"][b, h].astype(np.float64)
-        case["k"][b, h, pos, :] = (gamma * qv / np.linalg.norm(qv)).astype(np.float16)
+        case["k"][b, h // G, pos, :] = (gamma * qv / np.linalg.norm(qv)).astype(np.float16)
         planted.append((b, h, pos))
     return planted

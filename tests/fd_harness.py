@@ -28,6 +28,8 @@ class DeviceCase:
         assert self.ws_bytes > 0
         # garbage-filled so that nothing relies on a zeroed workspace
         self.ws = torch.full((self.ws_bytes,), 0xA5, dtype=torch.uint8, device=self.dev)
+        fdattn.fd_workspace_init(self.shape, *self._ws(), self._stream())
+        self.last_entry = None
         self.out = torch.full((case["B"], case["Hq"], case["D"]), float("nan"), dtype=torch.float16,
                               device=self.dev)
 
@@ -42,6 +44,7 @@ class DeviceCase:
 
     def run(self, entry="fd_decode_attn", phi=synth.PHI, bounds=synth.BOUNDS):
         self.out.fill_(float("nan"))
+        self.last_entry = entry
         if entry == "fd_decode_attn_sync":
             fdattn.fd_decode_attn_sync(*self._args(), self.out.data_ptr(), *self._ws(), self._stream())
         else:
@@ -64,6 +67,11 @@ class DeviceCase:
         B, Hq = self.case["B"], self.case["Hq"]
         chunk_flags = self._view(cf, self.rows * self.nc, np.uint8, (B, Hq, self.nc))
         row_flags = self._view(rf, self.rows, np.uint8, (B, Hq))
+        if self.last_entry != "fd_decode_attn_multikernel":
+            # the fused calls do not build the list themselves
+            fdattn.fd_list_flagged_rows(self.shape, self.seq_lens.data_ptr(), *self._ws(), self._stream())
+            torch.cuda.synchronize(self.dev)
+            assert np.array_equal(row_flags, self._view(rf, self.rows, np.uint8, (B, Hq)))
         n = int(self._view(cnt, 4, np.int32, (1,))[0])
         rows = self._view(lst, 4 * self.rows, np.int32, (self.rows,))[:max(n, 0)]
         return chunk_flags, row_flags, n, rows

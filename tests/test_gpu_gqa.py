@@ -1,0 +1,99 @@
+"""Grouped-query path (MFMA kernel): parity with the fp64 oracle, with the
+per-row path on explicitly repeated K/V, flags per query head, recomputation."""
+import numpy as np
+import pytest
+
+from paper_2311_01282_amd import synth
+
+pytestmark = pytest.mark.gpu
+LO, HI = synth.BOUNDS
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fd_harness
+    return fd_harness
+
+
+def exact(oracle, case):
+    return oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=8)
+
+
+CASES = [
+    # B, Hq, Hkv, Smax, lens, chunk
+    (2, 16, 2, 1024, [1024, 777], 256),     # the benchmark's group of 8
+    (1, 8, 2, 600, [555], 64),              # group of 4, small chunks, ragged tail
+    (2, 6, 3, 1500, [1500, 17], 512),       # group of 2, a 17-key sequence
+    (1, 16, 1, 2100, [2050], 1024),         # group of 16 (the tile is full), one short last chunk
+    (3, 12, 4, 700, [0, 700, 1], 128),      # group of 3 (not a power of two), an empty sequence
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Smax,lens,chunk", CASES)
+def test_gqa_matches_oracle_and_per_row_path(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
+    case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=400 + Smax + chunk, seq_lens=lens,
+                           poison_padding=True)
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk)
+    assert margin.min() > 1e-2 and not orf.any()
+    dc = H.DeviceCase(case, chunk=chunk)
+    got = dc.run("fd_decode_attn_gqa")
+    H.assert_close(got, want, "gqa")
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and n == 0
+    # the per-row path on K/V repeated for every query head must agree row by row
+    G = Hq // Hkv
+    rep = dict(case)
+    rep["k"] = np.ascontiguousarray(np.repeat(case["k"], G, axis=1))
+    rep["v"] = np.ascontiguousarray(np.repeat(case["v"], G, axis=1))
+    rep["Hkv"] = Hq
+    got_rows = H.DeviceCase(rep, chunk=chunk).run("fd_decode_attn")
+    assert np.abs(got - got_rows).max() <= 1e-3
+    H.assert_close(dc.run("fd_decode_attn"), want, "per-row path on shared KV heads")
+
+
+def test_gqa_partial_sums_match_eq4(oracle, H):
+    """The per-chunk numerators and denominators the MFMA kernel leaves behind."""
+    case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=1300, seed=410, seq_lens=[1300, 515],
+                           poison_padding=True)
+    _, onum, oden = oracle.attn_unified(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"],
+                                        synth.PHI, 256, return_partials=True)
+    dc = H.DeviceCase(case, chunk=256)
+    dc.run("fd_decode_attn_gqa")
+    num, den = dc.partials()
+    np.testing.assert_allclose(den, oden, rtol=2e-5, atol=0)
+    np.testing.assert_allclose(num, onum, rtol=0, atol=2e-5 * np.abs(oden).max())
+
+
+def test_gqa_flags_are_per_query_head_and_rows_recomputed(oracle, H):
+    case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=2048, seed=420, seq_lens=[2048, 1111],
+                           poison_padding=True)
+    planted = synth.plant_keys(case, 3, 36.0, seed=421, allow_shared_kv=True)
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, 256)
+    assert margin.min() > 1e-2
+    for b, h, _ in planted:
+        assert orf[b, h]
+    assert orf.sum() < orf.size                     # other heads of the groups stay unflagged
+    dc = H.DeviceCase(case, chunk=256)
+    for _ in range(2):                              # twice: the arrival counters must reset
+        got = dc.run("fd_decode_attn_gqa")
+        H.assert_close(got, want, "gqa + recompute")
+        cf, rf, n, rows = dc.flags()
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+        assert n == int(orf.sum()) and rows.tolist() == np.flatnonzero(orf.reshape(-1)).tolist()
+    for b, h, pos in planted:
+        np.testing.assert_allclose(got[b, h], case["v"][b, h // 8, pos].astype(np.float64), atol=2e-3)
+    # every row flagged through tight bounds: everything comes from the synchronized scheme
+    got = dc.run("fd_decode_attn_gqa", phi=0.0, bounds=(-0.5, 0.5))
+    assert dc.flags()[1].all()
+    H.assert_close(got, want, "gqa, all rows recomputed")
+
+
+def test_gqa_rejects_ungrouped_shapes(H):
+    from paper_2311_01282_amd import fdattn
+    case = synth.make_case(B=1, Hq=4, Hkv=4, D=128, Smax=256, seed=430)
+    dc = H.DeviceCase(case, chunk=256)
+    with pytest.raises(fdattn.FdError) as e:
+        dc.run("fd_decode_attn_gqa")
+    assert e.value.status == fdattn.FD_ERR_UNSUPPORTED

@@ -32,18 +32,22 @@ SMALL = [
 ]
 
 
+UNIFIED = ["fd_decode_attn", "fd_decode_attn_multikernel"]
+
+
 @pytest.mark.parametrize("B,Hq,Hkv,Smax,lens,chunk", SMALL)
 def test_unified_and_sync_match_oracle(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
     case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=100 + Smax + chunk,
                            seq_lens=lens, poison_padding=True)
     want = exact(oracle, case)
     dc = H.DeviceCase(case, chunk=chunk)
-    got = dc.run("fd_decode_attn")
-    H.assert_close(got, want, "unified")
-    cf, rf, n, rows = dc.flags()
     ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk)
     assert margin.min() > 1e-2
-    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and n == 0 and len(rows) == 0
+    for entry in UNIFIED:
+        got = dc.run(entry)
+        H.assert_close(got, want, entry)
+        cf, rf, n, rows = dc.flags()
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and n == 0 and len(rows) == 0
     got_sync = dc.run("fd_decode_attn_sync")
     H.assert_close(got_sync, want, "sync")
     assert np.abs(got - got_sync).max() <= 1e-3
@@ -73,13 +77,16 @@ def test_planted_keys_flag_and_recompute(oracle, H):
     ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, 256)
     assert margin.min() > 1e-2 and orf.sum() == 3
     dc = H.DeviceCase(case, chunk=256)
-    got = dc.run("fd_decode_attn")
-    H.assert_close(got, want, "unified + recompute")
-    cf, rf, n, rows = dc.flags()
-    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
-    assert n == 3 and rows.tolist() == sorted(b * 4 + h for b, h, _ in planted)
-    for b, h, pos in planted:                      # closed form: the row is its planted key's V row
-        np.testing.assert_allclose(got[b, h], case["v"][b, h, pos].astype(np.float64), atol=2e-3)
+    outs = {}
+    for entry in UNIFIED + UNIFIED[:1]:            # the fused call twice: its tickets must reset
+        got = outs[entry] = dc.run(entry)
+        H.assert_close(got, want, entry + " + recompute")
+        cf, rf, n, rows = dc.flags()
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+        assert n == 3 and rows.tolist() == sorted(b * 4 + h for b, h, _ in planted)
+        for b, h, pos in planted:                  # closed form: the row is its planted key's V row
+            np.testing.assert_allclose(got[b, h], case["v"][b, h, pos].astype(np.float64), atol=2e-3)
+    assert np.abs(outs[UNIFIED[0]] - outs[UNIFIED[1]]).max() <= 1e-3
     # gamma = 12 stays inside the bounds: nothing may be flagged
     case2 = synth.make_case(B=3, Hq=4, Hkv=4, D=128, Smax=2048, seed=300, seq_lens=[2048, 1500, 300])
     synth.plant_keys(case2, 3, 12.0, seed=301)
@@ -98,13 +105,14 @@ def test_every_row_flagged_and_lower_bound(oracle, H):
     for phi, bounds in ((3.0, (-1.5, 20.0)), (0.0, (-60.0, 0.75)), (0.0, (-0.5, 0.5))):
         ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], phi,
                                         bounds[0], bounds[1], 128)
-        got = dc.run("fd_decode_attn", phi=phi, bounds=bounds)
-        cf, rf, n, rows = dc.flags()
-        near = margin.min() <= 1e-4     # a logit within rounding distance of a bound: flags not comparable
-        assert near or (np.array_equal(cf, ocf) and np.array_equal(rf, orf))
-        assert n == int(rf.sum()) and rows.tolist() == np.flatnonzero(rf.reshape(-1)).tolist()
         assert orf.all()
-        H.assert_close(got, want, "all rows recomputed")
+        near = margin.min() <= 1e-4     # a logit within rounding distance of a bound: flags not comparable
+        for entry in UNIFIED:
+            got = dc.run(entry, phi=phi, bounds=bounds)
+            cf, rf, n, rows = dc.flags()
+            assert near or (np.array_equal(cf, ocf) and np.array_equal(rf, orf))
+            assert n == int(rf.sum()) and rows.tolist() == np.flatnonzero(rf.reshape(-1)).tolist()
+            H.assert_close(got, want, entry + ", all rows recomputed")
 
 
 def test_guard_equality_flags(oracle, H):
@@ -122,10 +130,11 @@ def test_guard_equality_flags(oracle, H):
     ocf, orf, _ = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], phi, lo, hi, 256)
     assert orf.reshape(-1).tolist() == [0, 1, 1, 0] and ocf[0, 1].tolist() == [0, 1] and ocf[0, 2].tolist() == [1, 0]
     dc = H.DeviceCase(case, chunk=256)
-    got = dc.run("fd_decode_attn", phi=phi, bounds=(lo, hi))
-    cf, rf, n, rows = dc.flags()
-    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and rows.tolist() == [1, 2]
-    H.assert_close(got, exact(oracle, case), "equality")
+    for entry in UNIFIED:
+        got = dc.run(entry, phi=phi, bounds=(lo, hi))
+        cf, rf, n, rows = dc.flags()
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and rows.tolist() == [1, 2]
+        H.assert_close(got, exact(oracle, case), entry + ", equality")
 
 
 def test_invariance_to_phi_and_chunk(oracle, H):

@@ -3,6 +3,7 @@
 #include "fd_internal.h"
 
 #include <cmath>
+#include <cstdlib>
 
 namespace {
 
@@ -95,6 +96,7 @@ fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const v
     p->G = sh->n_q_heads / sh->n_kv_heads;
     p->Smax = sh->max_seq; p->C = sh->chunk; p->nc = (int)L.nc; p->rows = (int)L.rows;
     p->scale = sh->scale; p->phi = 0.f; p->lo = 0.f; p->hi = 0.f;
+    p->elect = 0;
     return FD_OK;
 }
 
@@ -104,6 +106,21 @@ fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
         return FD_ERR_BOUNDS;
     p->phi = phi; p->lo = b.lo; p->hi = b.hi;
     return FD_OK;
+}
+
+// Whether the chunk kernel should finish the rows itself (one launch) or leave that
+// to a second, tiny launch.  Electing a finisher costs every workgroup two memory
+// round trips at its end (results performed, arrival counter); a second launch costs
+// about 3 us once.  Small grids are latency-bound, so they fuse; large grids keep
+// their workgroups streaming and pay the launch.  FD_ELECT=0/1 overrides (tuning).
+inline int elect_in_kernel(long long workgroups)
+{
+    static const int forced = [] {
+        const char *e = std::getenv("FD_ELECT");
+        return e ? (e[0] == '0' ? 0 : 1) : -1;
+    }();
+    if (forced >= 0) return forced;
+    return workgroups <= 1024;
 }
 
 #define FD_TRY(expr) do { if ((expr) != hipSuccess) return FD_ERR_HIP; } while (0)
@@ -168,7 +185,10 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
     st = set_guard(&p, phi, bounds);
     if (st != FD_OK) return st;
     if (p.rows == 0) return FD_OK;
-    FD_TRY(fd::launch_decode_fused(p, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    p.elect = elect_in_kernel((long long)p.rows * p.nc);
+    FD_TRY(fd::launch_decode_fused(p, s));
+    if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;
 }
 
@@ -183,7 +203,10 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
     if (st != FD_OK) return st;
     if (p.G < 2 || p.G > 16) return FD_ERR_UNSUPPORTED;
     if (p.rows == 0) return FD_OK;
-    FD_TRY(fd::launch_decode_fused_gqa(p, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc);
+    FD_TRY(fd::launch_decode_fused_gqa(p, s));
+    if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;
 }
 

@@ -8,13 +8,13 @@
 //            v_mfma_f32_16x16x32_f16: A = a 16-key block of K, B = Q padded to 16
 //            heads (zero rows), 4 instructions per block (d = 4 x 32).
 //   weights  P = e^{s S^T - phi} in fp32, in place in the accumulator layout
-//            (lane (head, g) holds keys 4g..4g+3 of the block) -- Eq. 4, no maximum.
+//            (lane (head, g) holds keys g, 4+g, 8+g, 12+g of the block) -- Eq. 4, no maximum.
 //            fp16 cannot hold e^{x-phi} over the admissible range of x - phi, so
 //            the second product stays in fp32:
 //   P.V      out[head][d] += sum_key P[head][key] V[key][d]
 //            v_mfma_f32_16x16x4_f32: A = P (one fp32 per lane: exactly the layout the
 //            score tile leaves behind), B = V converted to fp32.  Lane (n, g) loads
-//            the 16 bytes d = 8n..8n+7 of key 4g+r and feeds element e of them to
+//            the 16 bytes d = 8n..8n+7 of key 4r+g and feeds element e of them to
 //            accumulator tile e, so V needs no transpose either: 32 instructions
 //            per 16-key block.
 //
@@ -57,7 +57,7 @@ __device__ __forceinline__ void cvt8(const u32x4 &v, float (&o)[8])
 }
 
 template <int C>
-__global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Problem p)
+__global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const Problem p)
 {
     static_assert(sizeof(ChunkLds<4, C>) <= sizeof(float) * kTileFloats, "recompute workspace must fit the tile");
     __shared__ GqaLds lds;
@@ -85,9 +85,9 @@ __global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Pro
             const size_t slot = (size_t)(row0 + tid) * p.nc + c;
             p.ws.den[slot] = 0.f; p.ws.mloc[slot] = p.phi;
             p.ws.chunk_flags[slot] = 0; p.ws.chunk_state[slot] = 0;
-            if (nb == 0 && c == 0) p.ws.row_flags[row0 + tid] = 0;
+            if (nb == 0 && c == 0 && p.elect) p.ws.row_flags[row0 + tid] = 0;
         }
-        if (nb == 0 && c == 0)                 // empty sequence: nobody else owns these rows
+        if (nb == 0 && c == 0 && p.elect)      // empty sequence: nobody else owns these rows
             for (int i = tid; i < G * kHeadDim; i += kGqaThreads) p.out[(size_t)row0 * kHeadDim + i] = 0;
         return;
     }
@@ -115,35 +115,37 @@ __global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Pro
     bool bad = false;
     const bool head_on = n < G;
 
-#pragma unroll 1
-    for (int blk = wave; blk < NBLK; blk += 4) {
+    // Keys past the valid length re-read the last valid key and get weight zero.
+    auto issue = [&](int blk, u32x4 (&kk)[4], u32x4 (&vv)[4]) {
         const int k0 = blk * 16;
-        if (k0 >= nvalid) break;               // uniform per wavefront: rest is padding
-        // Keys past the valid length re-read the last valid key and get weight zero.
-        u32x4 kk[4], vv[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + (size_t)min(k0 + 4 * i + g, last) * 16);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + (size_t)min(k0 + 4 * g + r, last) * 16);
-
-        // K block -> LDS row (4i + g), 16-byte slot n ^ row; then out in the A layout:
-        // lane (n, g) takes slot (4kb + g) ^ n of row n.
+        for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + (size_t)min(k0 + 4 * r + g, last) * 16);
+    };
+    auto reduce = [&](int blk, const u32x4 (&kk)[4], const u32x4 (&vv)[4]) {
+        const int k0 = blk * 16;
+        // K block -> LDS row (4i + g), 16-byte slot n ^ row; then out in the A layout.
+        // Row i of the A operand is key pk = 4(i%4) + i/4 of the block, so that score
+        // register r of lane group g belongs to key 4r + g -- the key whose V row the
+        // same lane group fetched with load r (1 KiB contiguous per load).
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 4 * i + g;
             kst[r * 16 + (n ^ r)] = kk[i];
         }
+        const int pk = 4 * (n & 3) + (n >> 2);
         f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
-            const f16x8 ka = __builtin_bit_cast(f16x8, kst[n * 16 + ((4 * kb + g) ^ n)]);
+            const f16x8 ka = __builtin_bit_cast(f16x8, kst[pk * 16 + ((4 * kb + g) ^ pk)]);
             sc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kb], sc, 0, 0, 0);
         }
-        // sc[r] = <q_head n, k_key>, key = k0 + 4g + r.  Guard, then e^{x - phi}.
+        // sc[r] = <q_head n, k_key>, key = k0 + 4r + g.  Guard, then e^{x - phi}.
         float pw[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const bool valid = k0 + 4 * g + r <= last;
+            const bool valid = k0 + 4 * r + g <= last;
             const float d = sc[r] * scale + nphi;
             bad |= valid & head_on & !((d > lo) & (d < hi));
             const float e = __builtin_amdgcn_exp2f(d * kLog2e);
@@ -157,6 +159,32 @@ __global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Pro
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pw[r], ve[e], acc[e], 0, 0, 0);
+        }
+    };
+    // This wavefront's blocks are wave, wave + 4, ...; nmine of them hold a valid key.
+    // Two-stage software pipeline, steady state free of branches around loads.
+    const int nblk_valid = min(NBLK, (nvalid + 15) / 16);
+    const int nmine = nblk_valid > wave ? (nblk_valid - wave + 3) / 4 : 0;
+    if (nmine > 0) {
+        u32x4 kA[4], vA[4], kB[4], vB[4];
+        issue(wave, kA, vA);
+        int i = 0;
+#pragma unroll 1
+        for (; i + 2 < nmine; i += 2) {
+            issue(wave + 4 * (i + 1), kB, vB);
+            __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of the arithmetic
+            reduce(wave + 4 * i, kA, vA);
+            issue(wave + 4 * (i + 2), kA, vA);
+            __builtin_amdgcn_sched_barrier(0);
+            reduce(wave + 4 * (i + 1), kB, vB);
+        }
+        if (i + 2 == nmine) {
+            issue(wave + 4 * (i + 1), kB, vB);
+            __builtin_amdgcn_sched_barrier(0);
+            reduce(wave + 4 * i, kA, vA);
+            reduce(wave + 4 * (i + 1), kB, vB);
+        } else {
+            reduce(wave + 4 * i, kA, vA);
         }
     }
 
@@ -208,6 +236,7 @@ __global__ __launch_bounds__(kGqaThreads) void decode_fused_gqa_kernel(const Pro
         }
     }
 
+    if (!p.elect) return;                      // a row-epilogue launch follows
     // Publish, arrive, and let the last arrival of the group finish its G rows.
     wait_stores_performed();
     __syncthreads();

@@ -31,6 +31,8 @@ struct Problem {
     WsView ws;
     int B, Hq, Hkv, G, Smax, C, nc, rows;
     float scale, phi, lo, hi;
+    int elect;     // 1: chunk kernels elect a finisher per row and run the row epilogue themselves;
+                   // 0: a separate row-epilogue launch follows (no per-workgroup hand-over latency)
 };
 
 __device__ __forceinline__ int valid_len(const Problem &p, int b)
@@ -59,6 +61,7 @@ hipError_t launch_flag_reduce(const Problem &p, hipStream_t s);
 hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
 hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
 hipError_t launch_clear_tickets(const Problem &p, hipStream_t s);
+hipError_t launch_row_epilogue(const Problem &p, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
 hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s);
 // fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling

@@ -12,6 +12,17 @@ __global__ __launch_bounds__(256) void clear_tickets_kernel(int32_t *ticket, int
     if (i < n) ticket[i] = 0;
 }
 
+// The row epilogue as a launch of its own (one workgroup per row), used when the
+// chunk kernels run without electing a finisher.
+__global__ __launch_bounds__(256) void row_epilogue_kernel(const Problem p)
+{
+    __shared__ float scratch[256];
+    __shared__ float red[4];
+    const int row = blockIdx.x;
+    const int S = valid_len(p, row / p.Hq);
+    row_epilogue<4>(p, row, (S + p.C - 1) / p.C, scratch, red);
+}
+
 // Chunk flags -> row flags, ascending list of flagged rows, their count.
 // A single workgroup: the compaction is a block-wide prefix sum, no atomics.
 __global__ __launch_bounds__(1024) void flag_reduce_kernel(const Problem p)
@@ -99,6 +110,12 @@ hipError_t launch_clear_tickets(const Problem &p, hipStream_t s)
     const int n = p.rows * p.nc;
     if (n == 0) return hipSuccess;
     return launch(clear_tickets_kernel, dim3((n + 255) / 256), dim3(256), s, p.ws.ticket, n);
+}
+
+hipError_t launch_row_epilogue(const Problem &p, hipStream_t s)
+{
+    if (p.rows == 0) return hipSuccess;
+    return launch(row_epilogue_kernel, dim3(p.rows), dim3(256), s, p);
 }
 
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s)

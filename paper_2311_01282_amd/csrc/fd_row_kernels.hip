@@ -42,7 +42,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
 
     const bool flagged = chunk_body<C, NW, UP, false>(p, row, c, lds);
     if (c >= nb) {                             // padding chunk: zero partials were written
-        if (nb == 0 && c == 0) {               // empty sequence: nobody else owns the row
+        if (nb == 0 && c == 0 && p.elect) {    // empty sequence: nobody else owns the row
             if (tid < kHeadDim) p.out[(size_t)row * kHeadDim + tid] = 0;
             if (tid == 0) p.ws.row_flags[row] = 0;
         }
@@ -53,6 +53,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
         chunk_body<C, NW, UP, true>(p, row, c, lds);
     }
 
+    if (!p.elect) return;                      // a row-epilogue launch follows
     // Publish this chunk's results (written through by chunk_body), then arrive; the
     // last arrival owns the row and reads the others' results past the caches.
     wait_stores_performed();

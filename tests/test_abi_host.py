@@ -1,0 +1,127 @@
+"""Host-only checks of the C-ABI library: it loads without a GPU, exports every
+symbol the header declares, sizes workspaces as documented and rejects bad
+arguments before touching the device.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fdattn.h")
+
+
+@pytest.fixture(scope="module")
+def fdattn():
+    lib = os.path.join(ROOT, "paper_2311_01282_amd", "libfdattn.so")
+    if not os.path.exists(lib):          # build only if nothing is built
+        from paper_2311_01282_amd import build
+        build.build()
+    from paper_2311_01282_amd import fdattn as mod
+    return mod
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(fdattn):
+    names = declared_functions()
+    assert len(names) >= 10 and "fd_decode_attn" in names and "fd_decode_attn_gqa" in names
+    lib = ctypes.CDLL(fdattn.LIB_PATH)
+    for name in names:
+        assert hasattr(lib, name), "header declares %s but the library does not export it" % name
+    assert sorted(fdattn.EXPORTS) == names, "binding and header disagree on the entry points"
+
+
+def test_workspace_bytes(fdattn):
+    sh = fdattn.make_shape(1, 32, 32, 128, 8192, 256, 0.0884)
+    n = fdattn.fd_workspace_bytes(sh)
+    rows, nc = 32, 32
+    need = rows * nc * (128 * 4 + 4 + 4 + 1 + 4 + 4) + rows * (1 + 4) + 4
+    assert need <= n <= need + 16 * 256 and n % 256 == 0
+    # unsupported or invalid shapes give 0
+    assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0     # head_dim
+    assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 8192, 100, 0.1)) == 0    # chunk
+    assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0     # heads
+    assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 0, 256, 0.1)) == 0       # max_seq
+    # a ragged last chunk still gets a slot
+    a = fdattn.fd_workspace_bytes(fdattn.make_shape(2, 4, 4, 128, 1024, 256, 0.1))
+    b = fdattn.fd_workspace_bytes(fdattn.make_shape(2, 4, 4, 128, 1025, 256, 0.1))
+    assert b > a
+
+
+def call(fdattn, name, shape, ptrs, phi=3.0, bounds=(-60.0, 20.0), ws=(0x1000, 1 << 30)):
+    q, k, v, sl, out = ptrs
+    try:
+        if name == "fd_decode_attn_sync":
+            fdattn.fd_decode_attn_sync(shape, q, k, v, sl, out, *ws)
+        elif name == "fd_decode_attn_partial":
+            fdattn.fd_decode_attn_partial(shape, q, k, v, sl, phi, bounds, *ws)
+        else:
+            getattr(fdattn, name)(shape, q, k, v, sl, phi, bounds, out, *ws)
+    except fdattn.FdError as e:
+        return e.status
+    return fdattn.FD_OK
+
+
+@pytest.mark.parametrize("name", ["fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel",
+                                  "fd_decode_attn_sync", "fd_decode_attn_partial"])
+def test_bad_arguments_are_rejected_before_any_launch(fdattn, name):
+    """Fake but well-aligned addresses: every call must fail in host-side
+    validation (nothing is enqueued, so nothing can touch these addresses)."""
+    grouped = name == "fd_decode_attn_gqa"
+    good = fdattn.make_shape(1, 16 if grouped else 4, 2 if grouped else 4, 128, 1024, 256, 0.0884)
+    ptrs = (0x10000, 0x20000, 0x30000, 0x40000, 0x50000)
+    assert call(fdattn, name, good, (0,) + ptrs[1:]) == fdattn.FD_ERR_NULL
+    assert call(fdattn, name, good, ptrs[:3] + (0,) + ptrs[4:]) == fdattn.FD_ERR_NULL
+    assert call(fdattn, name, good, (0x10008,) + ptrs[1:]) == fdattn.FD_ERR_SHAPE          # misaligned q
+    assert call(fdattn, name, good, ptrs, ws=(0, 1 << 30)) == fdattn.FD_ERR_WORKSPACE
+    assert call(fdattn, name, good, ptrs, ws=(0x1010, 1 << 30)) == fdattn.FD_ERR_WORKSPACE  # 256-byte alignment
+    assert call(fdattn, name, good, ptrs, ws=(0x1000, 1024)) == fdattn.FD_ERR_WORKSPACE     # too small
+    bad_dim = fdattn.make_shape(1, 16 if grouped else 4, 2 if grouped else 4, 64, 1024, 256, 0.0884)
+    assert call(fdattn, name, bad_dim, ptrs) == fdattn.FD_ERR_UNSUPPORTED
+    bad_heads = fdattn.make_shape(1, 5, 2, 128, 1024, 256, 0.0884)
+    assert call(fdattn, name, bad_heads, ptrs) == fdattn.FD_ERR_SHAPE
+    if name not in ("fd_decode_attn_sync",):
+        assert call(fdattn, name, good, ptrs, bounds=(5.0, 5.0)) == fdattn.FD_ERR_BOUNDS
+        assert call(fdattn, name, good, ptrs, bounds=(float("nan"), 5.0)) == fdattn.FD_ERR_BOUNDS
+        assert call(fdattn, name, good, ptrs, phi=float("inf")) == fdattn.FD_ERR_BOUNDS
+    if name != "fd_decode_attn_partial" and name != "fd_decode_attn_sync":
+        pass
+    if name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel", "fd_decode_attn_sync"):
+        assert call(fdattn, name, good, ptrs[:4] + (0,)) == fdattn.FD_ERR_NULL               # out
+
+
+def test_gqa_entry_point_needs_a_group(fdattn):
+    ptrs = (0x10000, 0x20000, 0x30000, 0x40000, 0x50000)
+    ungrouped = fdattn.make_shape(1, 4, 4, 128, 1024, 256, 0.0884)
+    assert call(fdattn, "fd_decode_attn_gqa", ungrouped, ptrs) == fdattn.FD_ERR_UNSUPPORTED
+    too_wide = fdattn.make_shape(1, 32, 1, 128, 1024, 256, 0.0884)
+    assert call(fdattn, "fd_decode_attn_gqa", too_wide, ptrs) == fdattn.FD_ERR_UNSUPPORTED
+
+
+def test_an_empty_batch_is_a_no_op(fdattn):
+    ptrs = (0x10000, 0x20000, 0x30000, 0x40000, 0x50000)
+    empty = fdattn.make_shape(0, 4, 4, 128, 1024, 256, 0.0884)
+    assert fdattn.fd_workspace_bytes(empty) > 0
+    for name in ("fd_decode_attn", "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_decode_attn_partial"):
+        assert call(fdattn, name, empty, ptrs) == fdattn.FD_OK
+
+
+def test_status_strings_and_getters(fdattn):
+    for code in range(7):
+        assert fdattn.status_str(code).startswith("FD_")
+    assert "unknown" in fdattn.status_str(99)
+    sh = fdattn.make_shape(1, 4, 4, 128, 1024, 256, 0.0884)
+    n = fdattn.fd_workspace_bytes(sh)
+    base = 0x7000000000
+    cf, rf, cnt, lst = fdattn.fd_get_flags(sh, base, n)
+    num, den = fdattn.fd_get_partials(sh, base, n)
+    addrs = [num, den, cf, rf, lst, cnt]
+    assert all(base <= a < base + n for a in addrs) and len(set(addrs)) == 6
+    assert num == base and all(a % 256 == 0 for a in addrs)
+    with pytest.raises(fdattn.FdError):
+        fdattn.fd_get_flags(sh, base, 16)

@@ -3,17 +3,21 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--chunk C]
 
-A "step" is one complete ``fd_decode_attn`` call (partial sums + range guard,
-flag reduction, combine, fallback for flagged rows) on one layer's KV cache.
-The benchmark cycles through ``layers`` distinct KV caches (>= 1 GiB in total)
-so that no step finds its cache in the 256 MB last-level cache -- what a
-multi-layer model does for every generated token.  All inputs are resident in
-HBM before the clock starts.  Prints ONE JSON line.
+A "step" is one complete ``fd_decode_attn`` (or ``fd_decode_attn_gqa``) call --
+partial sums + range guard, recomputation of flagged chunks, row epilogue -- on
+one layer's KV cache.  The benchmark cycles through ``layers`` distinct KV caches
+(>= 1 GiB in total, 4 GiB at the default workload) so that no step finds its cache
+in the 256 MB last-level cache: what a multi-layer model does for every generated
+token.  All inputs are resident in HBM before the clock starts.  Prints ONE JSON
+line.
 
-``value`` is the effective KV-read rate of the whole call chain: valid K+V bytes
-of one layer divided by the mean time per step.  ``roofline`` times the dominant
-kernel (the unified-phi chunk kernel) alone with HIP events on the launch stream.
-``cpu_baseline`` times the fp64 oracle on the host cores for the same layer.
+``value`` is the effective KV-read rate of the whole call: valid K+V bytes of one
+layer divided by the mean time per step (``us_per_layer_step``).  ``roofline``
+times the dominant kernel (the chunk kernel) alone with HIP events on the launch
+stream and sets it against the HBM peak and against a plain streaming read of the
+same buffers.  ``cpu_baseline`` times the fp64 oracle on the host cores.
+Secondary measurements (``chunk_sweep``, ``sync_baseline``, ``overflow``) use
+shorter loops of their own after the timed region.
 """
 import argparse
 import json
@@ -38,6 +42,10 @@ def parse():
     ap.add_argument("--entry", default="auto", choices=["auto", "fd_decode_attn", "fd_decode_attn_gqa",
                                                         "fd_decode_attn_multikernel", "fd_decode_attn_sync"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline and overflow A/B")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run 8 plain device copies of 256 MiB (a kernel of known traffic, for scaling "
+                         "hardware counters collected over this command)")
     return ap.parse_args()
 
 
@@ -59,11 +67,13 @@ def main():
     torch.cuda.set_device(dev)
 
     cfg = dict(synth.CONFIGS[args.workload])
-    chunk = args.chunk or cfg["chunk"]
     B, Hq, Hkv, D, Smax = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"]
+    grouped = Hq != Hkv
     entry = args.entry
     if entry == "auto":
-        entry = "fd_decode_attn_gqa" if Hq != Hkv else "fd_decode_attn"
+        entry = "fd_decode_attn_gqa" if grouped else "fd_decode_attn"
+    default_chunk = {"c1_b1_h32_s8192": 512}.get(args.workload, cfg["chunk"])
+    chunk = args.chunk or default_chunk
 
     # ---- layer 0 from the seeded host generator (the oracle sees the same bits) ----
     case0 = synth.make_config(args.workload, layer=0)
@@ -72,8 +82,8 @@ def main():
     kv_bytes = valid_keys * Hkv * D * 2 * 2           # K and V, fp16
     padded_bytes = B * Hkv * Smax * D * 2 * 2
     layers = args.layers or max(2, min(64, -(-(1 << 30) // padded_bytes)))
-    if args.workload.startswith("c1"):
-        layers = args.layers or 32
+    if args.workload.startswith("c1") and not args.layers:
+        layers = 32
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(cfg["seed"])
@@ -87,34 +97,81 @@ def main():
             qs.append(torch.randn((B, Hq, D), generator=gen, device=dev, dtype=torch.float32).half())
             ks.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
             vs.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
+    # planted overflow keys (layer 0 has them from the host generator): same rows and
+    # positions in every other layer, gamma * q / |q| computed from that layer's q
+    planted = case0["planted"]
+    saved_keys = []
+    for layer in range(layers):
+        for (b, h, pos) in planted:
+            if layer > 0:
+                qv = qs[layer][b, h].float()
+                saved_keys.append((layer, b, h, pos, ks[layer][b, h, pos].clone()))
+                ks[layer][b, h, pos] = (cfg["plant_gamma"] * qv / qv.norm()).half()
     seq_lens = torch.from_numpy(seq_lens_np).to(dev)
-    shape = fdattn.make_shape(B, Hq, Hkv, D, Smax, chunk, case0["scale"])
-    ws_bytes = fdattn.fd_workspace_bytes(shape)
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
-    out = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     phi, bounds = synth.PHI, synth.BOUNDS
-    fdattn.fd_workspace_init(shape, ws.data_ptr(), ws_bytes, stream)
+    out = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
 
-    def step(i):
-        l = i % layers
-        if entry == "fd_decode_attn_sync":
-            fdattn.fd_decode_attn_sync(shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(),
-                                       seq_lens.data_ptr(), out.data_ptr(), ws.data_ptr(), ws_bytes, stream)
-        else:
-            getattr(fdattn, entry)(shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(),
-                                   seq_lens.data_ptr(), phi, bounds, out.data_ptr(), ws.data_ptr(),
-                                   ws_bytes, stream)
+    class Runner:
+        def __init__(self, chunk, entry):
+            self.entry = entry
+            self.shape = fdattn.make_shape(B, Hq, Hkv, D, Smax, chunk, case0["scale"])
+            self.ws_bytes = fdattn.fd_workspace_bytes(self.shape)
+            self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+            fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, stream)
+            rows_or_groups = B * (Hkv if entry == "fd_decode_attn_gqa" else Hq)
+            self.single_launch = rows_or_groups * (-(-Smax // chunk)) <= 1024 and entry in (
+                "fd_decode_attn", "fd_decode_attn_gqa")
 
-    def kernel_only(i):
-        l = i % layers
-        fdattn.fd_decode_attn_partial(shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(),
-                                      seq_lens.data_ptr(), phi, bounds, ws.data_ptr(), ws_bytes, stream)
+        def step(self, i):
+            l = i % layers
+            a = (self.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr())
+            if self.entry == "fd_decode_attn_sync":
+                fdattn.fd_decode_attn_sync(*a, out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, stream)
+            else:
+                getattr(fdattn, self.entry)(*a, phi, bounds, out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, stream)
+
+        def chunk_kernel(self, i):
+            l = i % layers
+            f = fdattn.fd_decode_attn_gqa_partial if self.entry == "fd_decode_attn_gqa" else fdattn.fd_decode_attn_partial
+            f(self.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr(), phi, bounds,
+              self.ws.data_ptr(), self.ws_bytes, stream)
+
+    def wall(fn, steps, warmup):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def events(fn, steps, warmup):
+        for i in range(warmup):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / steps
+
+    run = Runner(chunk, entry)
+    if args.calibrate_copy:
+        src = torch.ones(128 << 20, dtype=torch.float16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)          # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- correctness of what is being timed: layer 0 against the oracle ----
     from oracle import fd_oracle
     ncpu = min(os.cpu_count() or 1, 16)
-    step(0)
+    run.step(0)
     torch.cuda.synchronize()
     got = out.cpu().numpy().astype(np.float64)
     t0 = time.perf_counter()
@@ -125,59 +182,67 @@ def main():
         print("bench.py: GPU result differs from the oracle (max-abs %.3e)" % max_abs, file=sys.stderr)
         return 1
 
-    # ---- timed region: the whole call chain ----
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    sec_per_step = dt / args.steps
+    # ---- timed region: the whole call ----
+    sec_per_step = wall(run.step, args.steps, args.warmup)
     value = kv_bytes / sec_per_step / 1e9
 
+    short = max(50, args.steps // 4)
     # ---- dominant kernel alone, HIP events on the launch stream ----
     roofline = None
-    if entry == "fd_decode_attn":
-        kernel_only = step        # the whole method is one launch of decode_fused_kernel
-        for i in range(args.warmup):
-            kernel_only(i)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            kernel_only(i)
-        e1.record()
-        torch.cuda.synchronize()
-        k_sec = e0.elapsed_time(e1) * 1e-3 / args.steps
+    if entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
+        kname = ("decode_fused_gqa_kernel<%d>" if entry == "fd_decode_attn_gqa" else "decode_fused_kernel<%d>") % chunk
+        k_sec = events(run.step if run.single_launch else run.chunk_kernel, args.steps, args.warmup)
         achieved = kv_bytes / k_sec / 1e9
-        roofline = {"bound": "hbm", "kernel": "decode_fused_kernel<%d>" % chunk,
+        roofline = {"bound": "hbm", "kernel": kname,
+                    "launch": "the whole call (single launch)" if run.single_launch else
+                              "chunk kernel alone; the call adds one row-epilogue launch",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": round(achieved / HBM_PEAK_GBS, 4), "us_per_launch": round(k_sec * 1e6, 2),
                     "algorithmic_bytes_per_launch": kv_bytes, "traffic": None}
-
-    # ---- plain streaming read of the same K and V buffers: the measured ceiling ----
-    if roofline is not None and (B * Hkv * Smax * D * 2) % 65536 == 0:
-        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        # HBM bytes per launch from the committed rocprofv3 counter runs (same kernel and workload)
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+                t = json.load(f).get(args.workload)
+            if t and t["kernel"] == kname:
+                roofline["traffic"] = t["traffic_bytes"]
+                roofline["traffic_source"] = t["source"]
+        except (OSError, ValueError, KeyError):
+            pass
         nbytes_each = B * Hkv * Smax * D * 2
+        if nbytes_each % 65536 == 0 and valid_keys == B * Smax:
+            # plain streaming read of the same K and V buffers: the measured ceiling
+            sink = torch.zeros(1, dtype=torch.int32, device=dev)
+            p_sec = events(lambda i: fdattn.fd_probe_stream_read(ks[i % layers].data_ptr(), vs[i % layers].data_ptr(),
+                                                                  nbytes_each, sink.data_ptr(), stream),
+                           short, 10)
+            roofline["stream_read_ceiling_gbs"] = round(2 * nbytes_each / p_sec / 1e9, 1)
+            roofline["frac_of_stream_read_ceiling"] = round((kv_bytes / k_sec) / (2 * nbytes_each / p_sec), 4)
 
-        def probe(i):
-            l = i % layers
-            fdattn.fd_probe_stream_read(ks[l].data_ptr(), vs[l].data_ptr(), nbytes_each, sink.data_ptr(), stream)
-        for i in range(args.warmup):
-            probe(i)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            probe(i)
-        e1.record()
-        torch.cuda.synchronize()
-        p_sec = e0.elapsed_time(e1) * 1e-3 / args.steps
-        roofline["stream_read_ceiling_gbs"] = round(2 * nbytes_each / p_sec / 1e9, 1)
-        roofline["frac_of_stream_read_ceiling"] = round(
-            (kv_bytes / k_sec) / (2 * nbytes_each / p_sec), 4)
+    extras = {}
+    if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
+        # chunk sweep (us per layer-step of the whole call)
+        sweep = {}
+        for c in (256, 512, 1024):
+            r = run if c == chunk else Runner(c, entry)
+            sweep[str(c)] = round(wall(r.step, short, 10) * 1e6, 2)
+        extras["chunk_sweep_us"] = sweep
+        # the synchronized scheme on every row (Eq. 2): what the method replaces
+        rs = Runner(chunk, "fd_decode_attn_sync")
+        extras["sync_baseline_us"] = round(wall(rs.step, short, 10) * 1e6, 2)
+        if not grouped:
+            rm = Runner(chunk, "fd_decode_attn_multikernel")
+            extras["multikernel_chain_us"] = round(wall(rm.step, short, 10) * 1e6, 2)
+        if planted:
+            # overflow A/B on the same tensors: planted keys in, then taken out again
+            t_with = wall(run.step, short, 10)
+            for (b, h, pos), orig in zip(planted, case0["planted_original_keys"]):
+                ks[0][b, h, pos] = torch.from_numpy(orig).to(dev)
+            for (layer, b, h, pos, orig) in saved_keys:
+                ks[layer][b, h, pos] = orig
+            t_without = wall(run.step, short, 10)
+            extras["overflow"] = {"rows_flagged": len(planted), "rows": B * Hq,
+                                  "us_with": round(t_with * 1e6, 2), "us_without": round(t_without * 1e6, 2),
+                                  "overhead_pct": round(100.0 * (t_with / t_without - 1.0), 2)}
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -197,10 +262,12 @@ def main():
         "config": {"workload": args.workload, "entry": entry, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "max_seq": Smax, "valid_keys": valid_keys, "chunk": chunk,
                    "kv_bytes_per_step": kv_bytes, "layers_cycled": layers, "cache": "cold (rotating KV sets)",
-                   "phi": phi, "bounds": list(bounds), "kv_dtype": "f16"},
+                   "phi": phi, "bounds": list(bounds), "kv_dtype": "f16",
+                   "launches_per_step": 1 if run.single_launch else (5 if entry == "fd_decode_attn_multikernel" else 2)},
         "parity_max_abs_vs_oracle": max_abs,
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
+    line.update(extras)
     print(json.dumps(line))
     return 0
 

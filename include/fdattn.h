@@ -97,17 +97,20 @@ fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream
 
 /*
  * Asynchronized-softmax decode attention, one row at a time (Section 3), in
- * ONE kernel launch.  Per (row, chunk) workgroup:
+ * one kernel launch (two for large grids, see step 3).  Per (row, chunk) workgroup:
  *   1. logits, range guard, sum e^{x-phi} and sum e^{x-phi} v with no maximum
  *      and no rescaling                               (Eq. 4, inner sums);
  *   2. if the guard fired for this chunk, its partial softmax is recomputed at
  *      once with the chunk's own maximum: (m, l, f.V)  (Eq. 2; "Recomputation");
- *   3. the workgroup that completes a row last -- elected by one integer ticket
- *      per row, the sums themselves use no atomics and run in fixed order --
- *      forms the row: unflagged rows by the plain outer sums of Eq. 4, flagged
- *      rows by the synchronized update of Eq. 2 over all partial results, each
- *      rescaled from its own reference (phi, or the chunk maximum) to the row
- *      maximum of those references.
+ *   3. the workgroup that completes a row last -- elected by a small tree of
+ *      integer arrival counters per row; the sums themselves use no atomics and
+ *      run in fixed order -- forms the row: unflagged rows by the plain outer
+ *      sums of Eq. 4, flagged rows by the synchronized update of Eq. 2 over all
+ *      partial results, each rescaled from its own reference (phi, or the chunk
+ *      maximum) to the row maximum of those references.  For grids of more than
+ *      1024 workgroups step 3 runs as a second, tiny launch instead (one
+ *      workgroup per row, no counters): large grids are throughput-bound and the
+ *      election's two memory round trips per workgroup cost more than a launch.
  * A flagged row is thus produced by the synchronized scheme, but only the
  * partial vectors that left the bounds are re-read; the others already are
  * valid partial-softmax results relative to phi.  fd_decode_attn_multikernel
@@ -159,14 +162,19 @@ fd_status fd_decode_attn_sync(const fd_shape *shape, const void *q, const void *
                               void *out, fd_workspace ws, void *stream);
 
 /*
- * Step 1 of fd_decode_attn alone (Eq. 4, inner sums and the range guard):
- * fills the workspace's per-chunk numerators, denominators and chunk flags and
- * writes nothing else.  For tests of the partial sums and for timing the
- * dominant kernel on its own.
+ * The chunk stage of fd_decode_attn alone (steps 1 and 2 of its description: Eq. 4
+ * inner sums, the range guard, on-the-spot recomputation of flagged chunks): fills
+ * the workspace's per-chunk numerators, denominators, references and chunk flags
+ * and writes neither `out` nor the row flags.  For tests of the partial sums and
+ * for timing the dominant kernel on its own.  fd_decode_attn_gqa_partial is the
+ * same for the grouped kernel of fd_decode_attn_gqa.
  */
 fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const void *k_cache,
                                  const void *v_cache, const int32_t *seq_lens, float phi,
                                  fd_bounds bounds, fd_workspace ws, void *stream);
+fd_status fd_decode_attn_gqa_partial(const fd_shape *shape, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *seq_lens, float phi,
+                                     fd_bounds bounds, fd_workspace ws, void *stream);
 
 /*
  * Device pointers into `ws` to the flags of the last decode call that used it

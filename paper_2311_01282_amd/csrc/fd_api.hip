@@ -152,18 +152,37 @@ size_t fd_workspace_bytes(const fd_shape *shape)
     return plan(shape, &L) == FD_OK ? L.total : 0;
 }
 
-fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const void *k_cache,
-                                 const void *v_cache, const int32_t *seq_lens, float phi,
-                                 fd_bounds bounds, fd_workspace ws, void *stream)
+// The chunk kernel of fd_decode_attn / fd_decode_attn_gqa alone: no election, no
+// row epilogue.
+static fd_status partial_only(const fd_shape *shape, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *seq_lens, float phi,
+                              fd_bounds bounds, fd_workspace ws, void *stream, bool grouped)
 {
     fd::Problem p;
     fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, nullptr, false, ws, &p);
     if (st != FD_OK) return st;
     st = set_guard(&p, phi, bounds);
     if (st != FD_OK) return st;
+    if (grouped && (p.G < 2 || p.G > 16)) return FD_ERR_UNSUPPORTED;
     if (p.rows == 0) return FD_OK;
-    FD_TRY(fd::launch_partial_unified(p, static_cast<hipStream_t>(stream)));
+    p.elect = 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    FD_TRY(grouped ? fd::launch_decode_fused_gqa(p, s) : fd::launch_decode_fused(p, s));
     return FD_OK;
+}
+
+fd_status fd_decode_attn_partial(const fd_shape *shape, const void *q, const void *k_cache,
+                                 const void *v_cache, const int32_t *seq_lens, float phi,
+                                 fd_bounds bounds, fd_workspace ws, void *stream)
+{
+    return partial_only(shape, q, k_cache, v_cache, seq_lens, phi, bounds, ws, stream, false);
+}
+
+fd_status fd_decode_attn_gqa_partial(const fd_shape *shape, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *seq_lens, float phi,
+                                     fd_bounds bounds, fd_workspace ws, void *stream)
+{
+    return partial_only(shape, q, k_cache, v_cache, seq_lens, phi, bounds, ws, stream, true);
 }
 
 fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream)

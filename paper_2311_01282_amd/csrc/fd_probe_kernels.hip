@@ -1,6 +1,7 @@
 // Measurement aid: a plain streaming read of two buffers with the same launch
-// geometry and access pattern as the chunk kernel (256-thread workgroups, each
-// walking 64 KiB of each buffer with 128-bit loads) and no arithmetic beyond an
+// geometry and access pattern as the chunk kernel at 256 keys per chunk
+// (256-thread workgroups, each walking 64 KiB of each buffer with non-temporal
+// 128-bit loads, 4 KiB of each in flight per wavefront) and no arithmetic beyond an
 // XOR.  Its rate is the ceiling a read-only kernel of this shape reaches.
 #include "fd_internal.h"
 
@@ -11,20 +12,19 @@ constexpr int kTile = 65536;   // bytes of each buffer per workgroup
 
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *a, const uint4 *b, unsigned *sink)
 {
-    const size_t base = (size_t)blockIdx.x * (kTile / 16) + threadIdx.x;
-    uint4 acc = make_uint4(0, 0, 0, 0);
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 *pa = reinterpret_cast<const u32x4 *>(a) + (size_t)blockIdx.x * (kTile / 16) + threadIdx.x;
+    const u32x4 *pb = reinterpret_cast<const u32x4 *>(b) + (size_t)blockIdx.x * (kTile / 16) + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
 #pragma unroll 1
-    for (int i = 0; i < kTile / 16 / 256; i += 8) {
-        uint4 x[8], y[8];
+    for (int i = 0; i < kTile / 16 / 256; i += 4) {
+        u32x4 x[4], y[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = a[base + (size_t)(i + u) * 256];
+        for (int u = 0; u < 4; ++u) x[u] = __builtin_nontemporal_load(pa + (size_t)(i + u) * 256);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) y[u] = b[base + (size_t)(i + u) * 256];
+        for (int u = 0; u < 4; ++u) y[u] = __builtin_nontemporal_load(pb + (size_t)(i + u) * 256);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            acc.x ^= x[u].x ^ y[u].x; acc.y ^= x[u].y ^ y[u].y;
-            acc.z ^= x[u].z ^ y[u].z; acc.w ^= x[u].w ^ y[u].w;
-        }
+        for (int u = 0; u < 4; ++u) acc ^= x[u] ^ y[u];
     }
     const unsigned r = acc.x ^ acc.y ^ acc.z ^ acc.w;
     if (r == 0x9e3779b9u) sink[0] = r;   // practically never true: keeps the loads alive

@@ -56,8 +56,9 @@ for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikerne
     getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
 _lib.fd_decode_attn_sync.restype = ctypes.c_int
 _lib.fd_decode_attn_sync.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, Workspace, _vp]
-_lib.fd_decode_attn_partial.restype = ctypes.c_int
-_lib.fd_decode_attn_partial.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, Workspace, _vp]
+for _name in ("fd_decode_attn_partial", "fd_decode_attn_gqa_partial"):
+    getattr(_lib, _name).restype = ctypes.c_int
+    getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, Workspace, _vp]
 _lib.fd_get_flags.restype = ctypes.c_int
 _lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
 _lib.fd_get_partials.restype = ctypes.c_int
@@ -72,7 +73,7 @@ _lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 
 EXPORTS = ("fd_workspace_bytes", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
-           "fd_decode_attn_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
+           "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
 
 
@@ -125,6 +126,11 @@ def fd_decode_attn_sync(shape, q, k_cache, v_cache, seq_lens, out, ws_ptr, ws_by
 def fd_decode_attn_partial(shape, q, k_cache, v_cache, seq_lens, phi, bounds, ws_ptr, ws_bytes, stream=0):
     _check(_lib.fd_decode_attn_partial(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
                                        Bounds(*bounds), Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_gqa_partial(shape, q, k_cache, v_cache, seq_lens, phi, bounds, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_gqa_partial(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                                           Bounds(*bounds), Workspace(ws_ptr, ws_bytes), stream))
 
 
 def fd_get_flags(shape, ws_ptr, ws_bytes):

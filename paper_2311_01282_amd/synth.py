@@ -101,6 +101,7 @@ def plant_keys(case, n_rows, gamma, seed, allow_shared_kv=False):
     rows = case["B"] * case["Hq"]
     picked = rng.choice(rows, size=n_rows, replace=False)
     planted = []
+    originals = case.setdefault("planted_original_keys", [])
     for r in sorted(int(x) for x in picked):
         b, h = divmod(r, case["Hq"])
         n = int(np.clip(case["seq_lens"][b], 0, case["Smax"]))
@@ -108,6 +109,7 @@ def plant_keys(case, n_rows, gamma, seed, allow_shared_kv=False):
             continue
         pos = int(rng.integers(0, n))
         qv = case["q"][b, h].astype(np.float64)
+        originals.append(case["k"][b, h // G, pos, :].copy())
         case["k"][b, h // G, pos, :] = (gamma * qv / np.linalg.norm(qv)).astype(np.float16)
         planted.append((b, h, pos))
     return planted

@@ -286,9 +286,11 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
 // workgroups of the same launch, hence the coherent loads; these pass the caches,
 // so they are issued in batches before anything waits on them.
 // `scratch` is >= 256 floats of LDS, `red` >= NW floats.
-template <int NW>
+// COHERENT = false is for a launch of its own, where ordinary cached loads suffice.
+template <int NW, bool COHERENT>
 __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int nb, float *scratch, float *red)
 {
+    auto ld = [](const auto *ptr) { return COHERENT ? load_coherent(ptr) : *ptr; };
     constexpr int UB = 16;                      // chunks per thread and batch
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = (tid >> 7) & 1, t = tid & (kHeadDim - 1);
@@ -302,8 +304,8 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int nb, 
     float m = -INFINITY;
     int f = 0;
     for (int c = tid; c < nb; c += NW * 64) {
-        m = fmaxf(m, load_coherent(&ref[c]));
-        f |= load_coherent(&p.ws.chunk_state[r0 + c]);
+        m = fmaxf(m, ld(&ref[c]));
+        f |= ld(&p.ws.chunk_state[r0 + c]);
     }
     // first batch of partial results, issued before anything above is waited for
     float nv[UB], rv[UB], dv[UB];
@@ -312,9 +314,9 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int nb, 
         for (int i = 0; i < UB; ++i) {
             const int c = c0 + 2 * i + half;
             const bool on = worker && c < nb;
-            nv[i] = on ? load_coherent(&num[(size_t)c * kHeadDim]) : 0.f;
-            rv[i] = on ? load_coherent(&ref[c]) : -INFINITY;
-            dv[i] = on ? load_coherent(&den[c]) : 0.f;
+            nv[i] = on ? ld(&num[(size_t)c * kHeadDim]) : 0.f;
+            rv[i] = on ? ld(&ref[c]) : -INFINITY;
+            dv[i] = on ? ld(&den[c]) : 0.f;
         }
     };
     issue(0);

@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     __syncthreads();
     if (!lds.last) return;
     for (int h = 0; h < G; ++h) {
-        row_epilogue<4>(p, row0 + h, nb, lds.tile, lds.red);
+        row_epilogue<4, true>(p, row0 + h, nb, lds.tile, lds.red);
         __syncthreads();
     }
 }

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(256) void row_epilogue_kernel(const Problem p)
     __shared__ float red[4];
     const int row = blockIdx.x;
     const int S = valid_len(p, row / p.Hq);
-    row_epilogue<4>(p, row, (S + p.C - 1) / p.C, scratch, red);
+    row_epilogue<4, false>(p, row, (S + p.C - 1) / p.C, scratch, red);
 }
 
 // Chunk flags -> row flags, ascending list of flagged rows, their count.

@@ -11,7 +11,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t num, den, mloc, chunk_flags, chunk_state, row_flags, list, count, ticket, total;
+    size_t num, den, mloc, chunk_flags, meta, row_flags, list, count, ticket, total;
     long long rows, nc;
 };
 
@@ -38,7 +38,7 @@ fd_status plan(const fd_shape *sh, Layout *L)
     L->den = off;          off = align_up(off + slots * sizeof(float));
     L->mloc = off;         off = align_up(off + slots * sizeof(float));
     L->chunk_flags = off;  off = align_up(off + slots);
-    L->chunk_state = off;  off = align_up(off + slots * sizeof(int32_t));
+    L->meta = off;         off = align_up(off + slots * sizeof(fd::SlotMeta));
     L->row_flags = off;    off = align_up(off + (size_t)rows);
     L->list = off;         off = align_up(off + (size_t)rows * sizeof(int32_t));
     L->count = off;        off = align_up(off + sizeof(int32_t));
@@ -63,7 +63,7 @@ fd::WsView view(const Layout &L, fd_workspace ws)
     w.den = reinterpret_cast<float *>(base + L.den);
     w.mloc = reinterpret_cast<float *>(base + L.mloc);
     w.chunk_flags = reinterpret_cast<uint8_t *>(base + L.chunk_flags);
-    w.chunk_state = reinterpret_cast<int32_t *>(base + L.chunk_state);
+    w.meta = reinterpret_cast<fd::SlotMeta *>(base + L.meta);
     w.row_flags = reinterpret_cast<uint8_t *>(base + L.row_flags);
     w.list = reinterpret_cast<int32_t *>(base + L.list);
     w.count = reinterpret_cast<int32_t *>(base + L.count);

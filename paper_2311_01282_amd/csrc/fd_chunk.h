@@ -21,7 +21,9 @@ namespace fd {
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// (bit-casting a vector ELEMENT in place is unreliable: take the element by value first)
 __device__ __forceinline__ half2_t as_h2(uint32_t u) { return __builtin_bit_cast(half2_t, u); }
+__device__ __forceinline__ float as_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
 
 // 128-bit streaming load: the data is used once, keep it from displacing other lines.
 __device__ __forceinline__ u32x4 load_stream(const u32x4 *p) { return __builtin_nontemporal_load(p); }
@@ -81,6 +83,15 @@ __device__ __forceinline__ T load_coherent(const T *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// The (den, reference, flag) record of a slot, written through as two 8-byte words.
+__device__ __forceinline__ void store_meta(const Problem &p, size_t slot, float den, float ref, int flagged)
+{
+    unsigned long long *w = reinterpret_cast<unsigned long long *>(&p.ws.meta[slot]);
+    store_coherent(&w[0], (unsigned long long)__builtin_bit_cast(unsigned, den) |
+                              ((unsigned long long)__builtin_bit_cast(unsigned, ref) << 32));
+    store_coherent(&w[1], (unsigned long long)(unsigned)flagged);
+}
+
 // Wait until this thread's earlier stores are performed (vector memory counter at
 // zero); with write-through stores this is the release half of the hand-over.
 __device__ __forceinline__ void wait_stores_performed()
@@ -138,7 +149,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         if (tid == 0) {
             p.ws.den[slot] = 0.f;
             p.ws.mloc[slot] = SYNC ? -INFINITY : p.phi;
-            if (!SYNC) { p.ws.chunk_flags[slot] = 0; p.ws.chunk_state[slot] = 0; }
+            store_meta(p, slot, 0.f, p.phi, 0);
+            if (!SYNC) p.ws.chunk_flags[slot] = 0;
         }
         return false;
     }
@@ -266,10 +278,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int i = 0; i < NW * 4; ++i) s += lds.den[i];
         store_coherent(&p.ws.den[slot], s);
         store_coherent(&p.ws.mloc[slot], mc);
-        if (!SYNC) {
-            store_coherent(&p.ws.chunk_state[slot], flagged ? 1 : 0);
-            p.ws.chunk_flags[slot] = flagged ? 1 : 0;      // host-visible copy, read after the launch
-        }
+        store_meta(p, slot, s, mc, SYNC || flagged);       // a chunk is only recomputed because its guard fired
+        if (!SYNC) p.ws.chunk_flags[slot] = flagged ? 1 : 0;
     }
     return flagged;
 }
@@ -278,72 +288,107 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
 // threads do the arithmetic): the synchronized update of Eq. 2 over the row's
 // partial results, each scaled by its own reference r_c -- phi for chunks summed
 // with the unified factor, the chunk maximum for recomputed ones:
-//     m = max_c r_c,   out = sum_c e^{r_c-m} num_c / sum_c e^{r_c-m} den_c.
-// For a row without flags every r_c is phi, every factor is exactly 1 and the
-// expression IS the plain outer sum of Eq. 4 (same bits), so one code path serves
-// both.  Sums run in chunk order (even chunks, odd chunks, then the two halves): no
-// atomics on data, same bits on every run.  The partial results come from other
-// workgroups of the same launch, hence the coherent loads; these pass the caches,
-// so they are issued in batches before anything waits on them.
-// `scratch` is >= 256 floats of LDS, `red` >= NW floats.
-// COHERENT = false is for a launch of its own, where ordinary cached loads suffice.
-template <int NW, bool COHERENT>
-__device__ __forceinline__ void row_epilogue(const Problem &p, int row, int nb, float *scratch, float *red)
+//     m = max_c r_c,   out = sum_c e^{r_c-m} num_c / sum_c e^{r_c-m} den_c,
+// evaluated in one pass with a running maximum (partial sums are merged by the same
+// rule).  For a row without flags every r_c is phi, every factor is exactly 1 and
+// the expression IS the plain outer sum of Eq. 4, so one code path serves both.
+// Work split: 8 slices of 32 threads; slice k takes chunks k, k+8, ...; a thread
+// owns 4 consecutive output elements, so a chunk costs it one 16-byte load of the
+// numerator and one of the slot record.  Fixed summation order: no atomics on data,
+// same bits on every run.
+// Slots [0, n_load) are loaded (all of them hold defined values: chunks without a
+// valid key carry zeros), slots [0, nb) enter the result; passing n_load = nc lets
+// the loads start before the sequence length is known.
+// COHERENT: the partial results come from other workgroups of the same launch and
+// are read past the caches; false is for a launch of its own.
+// `scratch` is >= 8 * 128 + 16 floats of LDS.
+template <int NW, bool COHERENT, typename NbFn>
+__device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_load, NbFn nb_fn, float *scratch)
 {
-    auto ld = [](const auto *ptr) { return COHERENT ? load_coherent(ptr) : *ptr; };
-    constexpr int UB = 16;                      // chunks per thread and batch
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = (tid >> 7) & 1, t = tid & (kHeadDim - 1);
+    constexpr int UB = 4;                       // chunks per thread and batch (32 per batch over the 8 slices)
+    auto ld16 = [](const void *ptr) {
+        if constexpr (COHERENT) {
+            const unsigned long long *w = static_cast<const unsigned long long *>(ptr);
+            const unsigned long long a = load_coherent(&w[0]), b = load_coherent(&w[1]);
+            return u32x4{(unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32)};
+        } else {
+            return *static_cast<const u32x4 *>(ptr);
+        }
+    };
+    const int tid = threadIdx.x;
+    const int slice = (tid >> 5) & 7, t4 = tid & 31;
     const bool worker = tid < 256;
     const size_t r0 = (size_t)row * p.nc;
-    const float *num = p.ws.num + r0 * kHeadDim + t;
-    const float *den = p.ws.den + r0;
-    const float *ref = p.ws.mloc + r0;
+    const float *num = p.ws.num + r0 * kHeadDim + 4 * t4;
+    const SlotMeta *meta = p.ws.meta + r0;
 
-    // row maximum of the references and the row flag: one strided load per chunk
-    float m = -INFINITY;
-    int f = 0;
-    for (int c = tid; c < nb; c += NW * 64) {
-        m = fmaxf(m, ld(&ref[c]));
-        f |= ld(&p.ws.chunk_state[r0 + c]);
-    }
-    // first batch of partial results, issued before anything above is waited for
-    float nv[UB], rv[UB], dv[UB];
+    u32x4 nv[UB], mv[UB];
     auto issue = [&](int c0) {
 #pragma unroll
         for (int i = 0; i < UB; ++i) {
-            const int c = c0 + 2 * i + half;
-            const bool on = worker && c < nb;
-            nv[i] = on ? ld(&num[(size_t)c * kHeadDim]) : 0.f;
-            rv[i] = on ? ld(&ref[c]) : -INFINITY;
-            dv[i] = on ? ld(&den[c]) : 0.f;
+            const int c = c0 + 8 * i + slice;
+            const bool on = worker && c < n_load;
+            nv[i] = on ? ld16(num + (size_t)c * kHeadDim) : u32x4{0u, 0u, 0u, 0u};
+            mv[i] = on ? ld16(meta + c) : u32x4{0u, 0u, 0u, 0u};
         }
     };
     issue(0);
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) red[wave] = m;
-    const int rf = __syncthreads_or(f);
-    m = red[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) m = fmaxf(m, red[w]);
-
-    float s = 0.f, l = 0.f;
-    for (int c0 = 0; c0 < nb; c0 += 2 * UB) {
+    const int nb = nb_fn();                     // may be a load of its own, in flight with the batch
+    float m = -INFINITY, l = 0.f;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    int f = 0;
+    for (int c0 = 0; c0 < n_load; c0 += 8 * UB) {
         if (c0) issue(c0);
+        float r[UB], bm = -INFINITY;
 #pragma unroll
         for (int i = 0; i < UB; ++i) {
-            const float a = __builtin_amdgcn_exp2f((rv[i] - m) * kLog2e);   // exactly 1 when r_c == m
-            s = __builtin_fmaf(a, nv[i], s);
-            l = __builtin_fmaf(a, dv[i], l);
+            const bool in_row = c0 + 8 * i + slice < nb;
+            r[i] = in_row ? as_f32(mv[i][1]) : -INFINITY;
+            bm = fmaxf(bm, r[i]);
+            f |= in_row ? (int)mv[i][2] : 0;
+        }
+        if (bm > m) {                           // rescale what was summed so far (never for unflagged rows)
+            const float a = __builtin_amdgcn_exp2f((m - bm) * kLog2e);   // 0 on the first batch
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] *= a;
+            l *= a;
+            m = bm;
+        }
+#pragma unroll
+        for (int i = 0; i < UB; ++i) {
+            // exactly 1 when r_c == m; 0 for slots outside the row (their sums are finite)
+            const float a = r[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((r[i] - m) * kLog2e);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s[e] = __builtin_fmaf(a, as_f32(nv[i][e]), s[e]);
+            l = __builtin_fmaf(a, as_f32(mv[i][0]), l);
         }
     }
-    if (worker && half) { scratch[t] = s; scratch[kHeadDim + t] = l; }
-    __syncthreads();
-    if (worker && !half) {
-        s += scratch[t];
-        l += scratch[kHeadDim + t];
-        p.out[(size_t)row * kHeadDim + t] = nb > 0 ? to_half_bits(s / l) : (uint16_t)0;
+    // merge the 8 slices (slice order), divide, round to fp16
+    float *S = scratch, *L = scratch + 8 * kHeadDim, *M = L + 8;
+    if (worker) {
+        *reinterpret_cast<float4 *>(&S[slice * kHeadDim + 4 * t4]) = make_float4(s[0], s[1], s[2], s[3]);
+        if (t4 == 0) { L[slice] = l; M[slice] = m; }
+    }
+    const int rf = __syncthreads_or(f);
+    if (tid < 32) {
+        float mm = M[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) mm = fmaxf(mm, M[k]);
+        float o[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float a = M[k] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((M[k] - mm) * kLog2e);   // 1 for unflagged rows
+            const float4 v = *reinterpret_cast<const float4 *>(&S[k * kHeadDim + 4 * tid]);
+            o[0] = __builtin_fmaf(a, v.x, o[0]); o[1] = __builtin_fmaf(a, v.y, o[1]);
+            o[2] = __builtin_fmaf(a, v.z, o[2]); o[3] = __builtin_fmaf(a, v.w, o[3]);
+            lt = __builtin_fmaf(a, L[k], lt);
+        }
+        uint2 h = make_uint2(0u, 0u);
+        if (nb > 0) {
+            h.x = (unsigned)to_half_bits(o[0] / lt) | ((unsigned)to_half_bits(o[1] / lt) << 16);
+            h.y = (unsigned)to_half_bits(o[2] / lt) | ((unsigned)to_half_bits(o[3] / lt) << 16);
+        }
+        *reinterpret_cast<uint2 *>(p.out + (size_t)row * kHeadDim + 4 * tid) = h;
     }
     if (tid == 0) p.ws.row_flags[row] = rf ? 1 : 0;
 }

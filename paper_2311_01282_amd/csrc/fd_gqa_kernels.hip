@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         if (tid < G) {
             const size_t slot = (size_t)(row0 + tid) * p.nc + c;
             p.ws.den[slot] = 0.f; p.ws.mloc[slot] = p.phi;
-            p.ws.chunk_flags[slot] = 0; p.ws.chunk_state[slot] = 0;
+            p.ws.chunk_flags[slot] = 0; store_meta(p, slot, 0.f, p.phi, 0);
             if (nb == 0 && c == 0 && p.elect) p.ws.row_flags[row0 + tid] = 0;
         }
         if (nb == 0 && c == 0 && p.elect)      // empty sequence: nobody else owns these rows
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         const int f = (flagged_heads >> tid) & 1;
         store_coherent(&p.ws.den[slot], s);
         store_coherent(&p.ws.mloc[slot], p.phi);
-        store_coherent(&p.ws.chunk_state[slot], f);
+        store_meta(p, slot, s, p.phi, f);
         p.ws.chunk_flags[slot] = (uint8_t)f;
     }
 
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     __syncthreads();
     if (!lds.last) return;
     for (int h = 0; h < G; ++h) {
-        row_epilogue<4, true>(p, row0 + h, nb, lds.tile, lds.red);
+        row_epilogue<4, true>(p, row0 + h, nb, [nb] { return nb; }, lds.tile);
         __syncthreads();
     }
 }

@@ -11,13 +11,21 @@ namespace fd {
 constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
 constexpr float kLog2e = 1.4426950408889634f;
 
+// One record per (row, chunk) slot, read by the row epilogue with a single 16-byte
+// load: the slot's denominator, the reference its sums are scaled by (phi, or the
+// chunk maximum after a recomputation) and whether the chunk's guard fired.
+struct alignas(16) SlotMeta {
+    float den, ref;
+    int flagged, pad;
+};
+
 // Views into the caller's workspace.
 struct WsView {
     float   *num;          // [rows, nc, 128]  sum e^{x-phi} v   (or f.V of the synchronized scheme)
     float   *den;          // [rows, nc]       sum e^{x-phi}     (or l)
     float   *mloc;         // [rows, nc]       chunk maximum m (synchronized scheme only)
     uint8_t *chunk_flags;  // [rows, nc]
-    int32_t *chunk_state;  // [rows, nc]  the same flags as words, handed between workgroups of one launch
+    SlotMeta *meta;        // [rows, nc]  (den, reference, flag) handed to the row epilogue
     uint8_t *row_flags;    // [rows]
     int32_t *list;         // [rows]  flagged rows, ascending
     int32_t *count;        // [1]     number of flagged rows

@@ -16,11 +16,10 @@ __global__ __launch_bounds__(256) void clear_tickets_kernel(int32_t *ticket, int
 // chunk kernels run without electing a finisher.
 __global__ __launch_bounds__(256) void row_epilogue_kernel(const Problem p)
 {
-    __shared__ float scratch[256];
-    __shared__ float red[4];
+    __shared__ __attribute__((aligned(16))) float scratch[8 * kHeadDim + 16];
     const int row = blockIdx.x;
-    const int S = valid_len(p, row / p.Hq);
-    row_epilogue<4, false>(p, row, (S + p.C - 1) / p.C, scratch, red);
+    // every slot of the row holds defined values, so the loads need not wait for the length
+    row_epilogue<4, false>(p, row, p.nc, [&] { return (valid_len(p, row / p.Hq) + p.C - 1) / p.C; }, scratch);
 }
 
 // Chunk flags -> row flags, ascending list of flagged rows, their count.

@@ -61,7 +61,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     if (tid == 0) lds.last = arrive_and_elect(p, row, c, nb);
     __syncthreads();
     if (!lds.last) return;
-    row_epilogue<NW, true>(p, row, nb, &lds.acc[0][0], lds.mx);
+    row_epilogue<NW, true>(p, row, nb, [nb] { return nb; }, &lds.acc[0][0]);
 }
 
 template <int C>

@@ -40,7 +40,7 @@ def test_workspace_bytes(fdattn):
     sh = fdattn.make_shape(1, 32, 32, 128, 8192, 256, 0.0884)
     n = fdattn.fd_workspace_bytes(sh)
     rows, nc = 32, 32
-    need = rows * nc * (128 * 4 + 4 + 4 + 1 + 4 + 4) + rows * (1 + 4) + 4
+    need = rows * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4) + rows * (1 + 4) + 4
     assert need <= n <= need + 16 * 256 and n % 256 == 0
     # unsupported or invalid shapes give 0
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0     # head_dim

@@ -72,7 +72,8 @@ def main():
     entry = args.entry
     if entry == "auto":
         entry = "fd_decode_attn_gqa" if grouped else "fd_decode_attn"
-    default_chunk = {"c1_b1_h32_s8192": 512}.get(args.workload, cfg["chunk"])
+    # the 8K workload sweeps {256, 512, 1024}; the headline uses the best of them
+    default_chunk = {"c1_b1_h32_s8192": 1024}.get(args.workload, cfg["chunk"])
     chunk = args.chunk or default_chunk
 
     # ---- layer 0 from the seeded host generator (the oracle sees the same bits) ----
@@ -119,9 +120,9 @@ def main():
             self.ws_bytes = fdattn.fd_workspace_bytes(self.shape)
             self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
             fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, stream)
-            rows_or_groups = B * (Hkv if entry == "fd_decode_attn_gqa" else Hq)
-            self.single_launch = rows_or_groups * (-(-Smax // chunk)) <= 1024 and entry in (
-                "fd_decode_attn", "fd_decode_attn_gqa")
+            gqa = entry == "fd_decode_attn_gqa"
+            wgs = B * (Hkv if gqa else Hq) * (-(-Smax // chunk))
+            self.single_launch = wgs <= (256 if gqa else 1024) and entry in ("fd_decode_attn", "fd_decode_attn_gqa")
 
         def step(self, i):
             l = i % layers

@@ -108,9 +108,10 @@ fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream
  *      sums of Eq. 4, flagged rows by the synchronized update of Eq. 2 over all
  *      partial results, each rescaled from its own reference (phi, or the chunk
  *      maximum) to the row maximum of those references.  For grids of more than
- *      1024 workgroups step 3 runs as a second, tiny launch instead (one
- *      workgroup per row, no counters): large grids are throughput-bound and the
- *      election's two memory round trips per workgroup cost more than a launch.
+ *      1024 workgroups (256 for fd_decode_attn_gqa) step 3 runs as a second, tiny
+ *      launch instead (one workgroup per row, no counters): large grids are
+ *      throughput-bound and the election's two memory round trips per workgroup
+ *      cost more than a launch.
  * A flagged row is thus produced by the synchronized scheme, but only the
  * partial vectors that left the bounds are re-read; the others already are
  * valid partial-softmax results relative to phi.  fd_decode_attn_multikernel

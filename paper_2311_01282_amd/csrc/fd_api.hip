@@ -113,14 +113,14 @@ fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
 // round trips at its end (results performed, arrival counter); a second launch costs
 // about 3 us once.  Small grids are latency-bound, so they fuse; large grids keep
 // their workgroups streaming and pay the launch.  FD_ELECT=0/1 overrides (tuning).
-inline int elect_in_kernel(long long workgroups)
+inline int elect_in_kernel(long long workgroups, long long limit = 1024)
 {
     static const int forced = [] {
         const char *e = std::getenv("FD_ELECT");
         return e ? (e[0] == '0' ? 0 : 1) : -1;
     }();
     if (forced >= 0) return forced;
-    return workgroups <= 1024;
+    return workgroups <= limit;
 }
 
 #define FD_TRY(expr) do { if ((expr) != hipSuccess) return FD_ERR_HIP; } while (0)
@@ -223,7 +223,8 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
     if (p.G < 2 || p.G > 16) return FD_ERR_UNSUPPORTED;
     if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc);
+    // the grouped kernel holds fewer workgroups per CU, so the election hurts it sooner
+    p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
     FD_TRY(fd::launch_decode_fused_gqa(p, s));
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;

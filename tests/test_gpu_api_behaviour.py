@@ -1,0 +1,102 @@
+"""Behaviour of the C ABI beyond the arithmetic: workspace reuse across shapes and
+entry points, non-default streams, back-to-back calls without synchronisation,
+the flag-list and read-probe calls."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2311_01282_amd import fdattn, synth
+
+pytestmark = pytest.mark.gpu
+LO, HI = synth.BOUNDS
+
+
+@pytest.fixture(scope="module")
+def H():
+    import fd_harness
+    return fd_harness
+
+
+def test_one_workspace_many_calls_and_shapes(oracle, H):
+    """One allocation serves different chunk sizes, entry points and problem shapes in
+    turn; it is re-initialised whenever the shape changes (the layout depends on it),
+    and repeated calls with one shape need no re-initialisation."""
+    big = synth.make_case(B=2, Hq=4, Hkv=4, D=128, Smax=2048, seed=500, seq_lens=[2048, 900])
+    small = synth.make_case(B=1, Hq=8, Hkv=2, D=128, Smax=640, seed=501, seq_lens=[600])
+    synth.plant_keys(big, 2, 36.0, seed=502)
+    dev = torch.device("cuda:0")
+    nbytes = max(fdattn.fd_workspace_bytes(fdattn.make_shape(2, 4, 4, 128, 2048, 64, big["scale"])),
+                 fdattn.fd_workspace_bytes(fdattn.make_shape(1, 8, 2, 128, 640, 64, small["scale"])))
+    ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    last_shape = None
+    want = {id(big): oracle.attn_exact(big["q"], big["k"], big["v"], big["seq_lens"], big["scale"]),
+            id(small): oracle.attn_exact(small["q"], small["k"], small["v"], small["seq_lens"], small["scale"])}
+    dev_t = {}
+    for case in (big, small):
+        dev_t[id(case)] = tuple(torch.from_numpy(np.ascontiguousarray(case[n])).to(dev) for n in ("q", "k", "v")) + (
+            torch.from_numpy(case["seq_lens"]).to(dev),)
+    plan = [(big, "fd_decode_attn", 256), (small, "fd_decode_attn_gqa", 128), (big, "fd_decode_attn", 64),
+            (small, "fd_decode_attn", 64), (big, "fd_decode_attn_multikernel", 512), (small, "fd_decode_attn_gqa", 64),
+            (big, "fd_decode_attn", 1024), (big, "fd_decode_attn", 1024), (big, "fd_decode_attn_multikernel", 1024),
+            (big, "fd_decode_attn", 1024)]
+    for case, entry, chunk in plan:
+        q, k, v, sl = dev_t[id(case)]
+        shape = fdattn.make_shape(case["B"], case["Hq"], case["Hkv"], 128, case["Smax"], chunk, case["scale"])
+        assert fdattn.fd_workspace_bytes(shape) <= nbytes
+        key = (case["B"], case["Hq"], case["Hkv"], case["Smax"], chunk)
+        if key != last_shape:
+            fdattn.fd_workspace_init(shape, ws.data_ptr(), nbytes, stream)
+            last_shape = key
+        out = torch.full((case["B"], case["Hq"], 128), float("nan"), dtype=torch.float16, device=dev)
+        getattr(fdattn, entry)(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), synth.PHI,
+                               synth.BOUNDS, out.data_ptr(), ws.data_ptr(), nbytes, stream)
+        torch.cuda.synchronize()
+        H.assert_close(out.cpu().numpy().astype(np.float64), want[id(case)], "%s chunk %d" % (entry, chunk))
+
+
+def test_side_stream_and_back_to_back_calls(oracle, H):
+    """Calls are enqueued on the stream they are given and need no synchronisation
+    between them: 20 calls on a side stream into distinct outputs, one sync at the end."""
+    case = synth.make_case(B=2, Hq=4, Hkv=4, D=128, Smax=1536, seed=510, seq_lens=[1536, 1000])
+    want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"])
+    dc = H.DeviceCase(case, chunk=256)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    outs = [torch.full_like(dc.out, float("nan")) for _ in range(20)]
+    with torch.cuda.stream(side):
+        for o in outs:
+            fdattn.fd_decode_attn(dc.shape, dc.q.data_ptr(), dc.k.data_ptr(), dc.v.data_ptr(), dc.seq_lens.data_ptr(),
+                                  synth.PHI, synth.BOUNDS, o.data_ptr(), dc.ws.data_ptr(), dc.ws_bytes, side.cuda_stream)
+    side.synchronize()
+    first = outs[0].cpu().numpy()
+    H.assert_close(first.astype(np.float64), want, "side stream")
+    for o in outs[1:]:
+        assert np.array_equal(o.cpu().numpy(), first)      # fixed summation order: same bits every time
+
+
+def test_flag_list_call_and_read_probe(oracle, H):
+    case = synth.make_case(B=2, Hq=4, Hkv=4, D=128, Smax=1024, seed=520)
+    planted = synth.plant_keys(case, 3, 36.0, seed=521)
+    dc = H.DeviceCase(case, chunk=128)
+    dc.run("fd_decode_attn")
+    cf, rf, n, rows = dc.flags()                       # runs fd_list_flagged_rows
+    assert n == 3 and rows.tolist() == sorted(b * 4 + h for b, h, _ in planted)
+    assert rf.reshape(-1)[rows].all() and rf.sum() == 3
+    # the probe only reads; it must accept the K and V buffers and reject odd sizes
+    sink = torch.zeros(1, dtype=torch.int32, device=dc.dev)
+    nbytes = dc.k.numel() * 2
+    fdattn.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes, sink.data_ptr(), 0)
+    torch.cuda.synchronize()
+    with pytest.raises(fdattn.FdError):
+        fdattn.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes - 2, sink.data_ptr(), 0)
+
+
+@pytest.mark.parametrize("Smax,lens,chunk", [(100, [100], 256), (64, [1], 64), (300, [299], 1024), (4097, [4097], 512)])
+def test_odd_sizes(oracle, H, Smax, lens, chunk):
+    """Padded lengths that are no multiple of the chunk, a cache shorter than one chunk."""
+    case = synth.make_case(B=1, Hq=3, Hkv=3, D=128, Smax=Smax, seed=530 + Smax, seq_lens=lens, poison_padding=True)
+    want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"])
+    dc = H.DeviceCase(case, chunk=chunk)
+    for entry in ("fd_decode_attn", "fd_decode_attn_multikernel", "fd_decode_attn_sync"):
+        H.assert_close(dc.run(entry), want, entry)

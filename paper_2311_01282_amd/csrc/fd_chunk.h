@@ -92,6 +92,14 @@ __device__ __forceinline__ void store_meta(const Problem &p, size_t slot, float 
     store_coherent(&w[1], (unsigned long long)(unsigned)flagged);
 }
 
+// Four consecutive floats written through as two 8-byte words (16-byte aligned).
+__device__ __forceinline__ void store_coherent4(float *ptr, float a, float b, float c, float d)
+{
+    unsigned long long *w = reinterpret_cast<unsigned long long *>(ptr);
+    store_coherent(&w[0], (unsigned long long)__builtin_bit_cast(unsigned, a) | ((unsigned long long)__builtin_bit_cast(unsigned, b) << 32));
+    store_coherent(&w[1], (unsigned long long)__builtin_bit_cast(unsigned, c) | ((unsigned long long)__builtin_bit_cast(unsigned, d) << 32));
+}
+
 // Wait until this thread's earlier stores are performed (vector memory counter at
 // zero); with write-through stores this is the release half of the hand-over.
 __device__ __forceinline__ void wait_stores_performed()

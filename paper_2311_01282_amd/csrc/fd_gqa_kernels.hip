@@ -204,9 +204,19 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     lds.den[wave][lane] = den;
     if (lane == 0) lds.bad[wave] = bad_mask;
     __syncthreads();
-    for (int i = tid; i < G * kHeadDim; i += kGqaThreads) {
-        const float s = lds.tile[i] + lds.tile[16 * kHeadDim + i] + lds.tile[32 * kHeadDim + i] + lds.tile[48 * kHeadDim + i];
-        store_coherent(&p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + (i & (kHeadDim - 1))], s);
+    // 4 consecutive elements per thread: one 16-byte LDS read per wavefront tile, 16 bytes out
+    for (int i = 4 * tid; i < G * kHeadDim; i += 4 * kGqaThreads) {
+        const float4 a = *reinterpret_cast<const float4 *>(&lds.tile[i]);
+        const float4 b = *reinterpret_cast<const float4 *>(&lds.tile[16 * kHeadDim + i]);
+        const float4 cc = *reinterpret_cast<const float4 *>(&lds.tile[32 * kHeadDim + i]);
+        const float4 d = *reinterpret_cast<const float4 *>(&lds.tile[48 * kHeadDim + i]);
+        float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + (i & (kHeadDim - 1))];
+        if (p.elect) {      // read by another workgroup of this launch: write through
+            store_coherent4(dst, a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y, a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
+        } else {
+            *reinterpret_cast<float4 *>(dst) = make_float4(a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y,
+                                                           a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
+        }
     }
     const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
     // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so

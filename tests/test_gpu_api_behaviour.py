@@ -100,3 +100,26 @@ def test_odd_sizes(oracle, H, Smax, lens, chunk):
     dc = H.DeviceCase(case, chunk=chunk)
     for entry in ("fd_decode_attn", "fd_decode_attn_multikernel", "fd_decode_attn_sync"):
         H.assert_close(dc.run(entry), want, entry)
+
+
+def test_hand_over_is_stable_over_many_calls(oracle, H):
+    """The single-launch kernel hands partial results between workgroups of one launch.
+    600 back-to-back calls on the 8K shape, alternating two KV caches, must reproduce
+    the first results bit for bit (a stale read of a partial result would not)."""
+    cases = [synth.make_config("c1_b1_h32_s8192", layer=l) for l in (0, 1)]
+    dcs = [H.DeviceCase(c, chunk=1024) for c in cases]
+    ref = [dc.run("fd_decode_attn") for dc in dcs]
+    for c, r in zip(cases, ref):
+        H.assert_close(r, oracle.attn_exact(c["q"], c["k"], c["v"], c["seq_lens"], c["scale"], nthreads=16), "c1")
+    dev = dcs[0].dev
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    n = 600
+    outs = torch.empty((n,) + tuple(dcs[0].out.shape), dtype=torch.float16, device=dev)
+    for i in range(n):
+        dc = dcs[i % 2]
+        fdattn.fd_decode_attn(dc.shape, dc.q.data_ptr(), dc.k.data_ptr(), dc.v.data_ptr(), dc.seq_lens.data_ptr(),
+                              synth.PHI, synth.BOUNDS, outs[i].data_ptr(), dcs[0].ws.data_ptr(), dcs[0].ws_bytes, stream)
+    torch.cuda.synchronize()
+    got = outs.cpu().numpy().astype(np.float64)
+    for i in range(n):
+        assert np.array_equal(got[i], ref[i % 2]), "call %d differs from the first call on the same cache" % i

@@ -265,9 +265,11 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     }
 
     // Workgroup reduction: NW*4 partial vectors (NW wavefronts x 4 keys per group).
-    float4 *dst = reinterpret_cast<float4 *>(&lds.acc[wave * 4 + sub][seg * 8]);
-    dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+    // LDS row layout: elements 8s..8s+3 at 4s, elements 8s+4..8s+7 at 64 + 4((s + 4) & 15). Both the
+    // 16-byte writes here and the 4-byte reads below then touch every bank once per pass.
+    float *arow = lds.acc[wave * 4 + sub];
+    *reinterpret_cast<float4 *>(&arow[4 * seg]) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    *reinterpret_cast<float4 *>(&arow[64 + 4 * ((seg + 4) & 15)]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
     if (seg == 0) lds.den[wave * 4 + sub] = den;
     __syncthreads();
     bool flagged = false;
@@ -276,9 +278,11 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int w = 0; w < NW; ++w) flagged |= lds.flag[w] != 0;
     }
     if (tid < kHeadDim) {
+        const int es = tid >> 3;                   // element tid sits in 16-byte segment es
+        const int pos = (tid & 4) ? 64 + 4 * ((es + 4) & 15) + (tid & 3) : 4 * es + (tid & 3);
         float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < NW * 4; ++i) s += lds.acc[i][tid];
+        for (int i = 0; i < NW * 4; ++i) s += lds.acc[i][pos];
         store_coherent(&p.ws.num[slot * kHeadDim + tid], s);
     } else if (tid == kHeadDim) {
         float s = 0.f;

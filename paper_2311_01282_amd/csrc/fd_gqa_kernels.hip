@@ -129,16 +129,20 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         // Row i of the A operand is key pk = 4(i%4) + i/4 of the block, so that score
         // register r of lane group g belongs to key 4r + g -- the key whose V row the
         // same lane group fetched with load r (1 KiB contiguous per load).
+        // Swizzle key swz(r) = the two 2-bit halves of r swapped: the 16 rows a read touches
+        // get 16 different keys, and any 8 consecutive lanes get keys that differ modulo 8,
+        // so 16-byte accesses are conflict-free whether the LDS serves 8 or 16 lanes a cycle.
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 4 * i + g;
-            kst[r * 16 + (n ^ r)] = kk[i];
+            kst[r * 16 + (n ^ (i | (g << 2)))] = kk[i];
         }
         const int pk = 4 * (n & 3) + (n >> 2);
+        const int pswz = n;                            // swz(pk) = (pk >> 2) | ((pk & 3) << 2) = n
         f32x4 sc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
-            const f16x8 ka = __builtin_bit_cast(f16x8, kst[pk * 16 + ((4 * kb + g) ^ pk)]);
+            const f16x8 ka = __builtin_bit_cast(f16x8, kst[pk * 16 + ((4 * kb + g) ^ pswz)]);
             sc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kb], sc, 0, 0, 0);
         }
         // sc[r] = <q_head n, k_key>, key = k0 + 4r + g.  Guard, then e^{x - phi}.
@@ -196,9 +200,11 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     for (int r = 0; r < 4; ++r) {
         const int h = 4 * g + r;
         if (h < G) {
-            float4 *dst = reinterpret_cast<float4 *>(&lds.tile[(wave * 16 + h) * kHeadDim + 8 * n]);
+            // Row layout in LDS: elements 8n..8n+3 at 4n, elements 8n+4..8n+7 at 64 + 4n, so that
+            // consecutive lanes write consecutive 16-byte slots (no bank conflicts).
+            float4 *dst = reinterpret_cast<float4 *>(&lds.tile[(wave * 16 + h) * kHeadDim + 4 * n]);
             dst[0] = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
-            dst[1] = make_float4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
+            dst[16] = make_float4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
         }
     }
     lds.den[wave][lane] = den;
@@ -210,7 +216,8 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         const float4 b = *reinterpret_cast<const float4 *>(&lds.tile[16 * kHeadDim + i]);
         const float4 cc = *reinterpret_cast<const float4 *>(&lds.tile[32 * kHeadDim + i]);
         const float4 d = *reinterpret_cast<const float4 *>(&lds.tile[48 * kHeadDim + i]);
-        float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + (i & (kHeadDim - 1))];
+        const int q = i & (kHeadDim - 1);      // LDS position -> element index (see the layout above)
+        float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + 2 * (q & 63) + 4 * (q >> 6)];
         if (p.elect) {      // read by another workgroup of this launch: write through
             store_coherent4(dst, a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y, a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
         } else {

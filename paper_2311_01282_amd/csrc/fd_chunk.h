@@ -133,9 +133,46 @@ struct ChunkLds {
 //                   den, mloc = m and leaves chunk_flags alone.
 // UP = groups of 4 keys per wavefront per pipeline stage.
 // Returns (uniformly over the workgroup) whether the guard fired (false for SYNC).
-template <int C, int NW, int UP, bool SYNC, int XN>
-__device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds)
+// Pins the kernel arguments the chunk loop needs into scalar registers at this point,
+// so that their loads leave in one batch at the top of the kernel.  Left alone the
+// compiler fetches each cache line of the argument block where it is first used --
+// behind the early-exit test, behind the index arithmetic -- and a fresh wavefront
+// then pays three dependent memory latencies instead of one.
+__device__ __forceinline__ void fetch_arguments_now(const Problem &p)
 {
+    asm volatile("" ::"s"(p.q), "s"(p.k), "s"(p.v), "s"(p.seq_lens), "s"(p.Hq), "s"(p.G), "s"(p.Hkv), "s"(p.Smax),
+                 "s"(p.nc), "s"(p.rows));
+}
+
+// The sequence length through a vector load, in two halves.  Scalar loads return out
+// of order, so waiting for any of them waits for all: a scalar length load would be
+// waited for together with the kernel arguments, before the first K/V load can go
+// out.  Vector loads return in order; this one stays in flight behind the loads
+// issued between the two halves.  (The opaque zero keeps the compiler from proving
+// the address uniform and turning the load back into a scalar one.)
+__device__ __forceinline__ int seq_len_issue(const Problem &p, int b)
+{
+    int zero;
+    asm("v_mov_b32 %0, 0" : "=v"(zero));
+    return p.seq_lens[b + zero];
+}
+__device__ __forceinline__ int seq_len_finish(const Problem &p, int raw)
+{
+    int S = __builtin_amdgcn_readfirstlane(raw);
+    S = S < 0 ? 0 : S;
+    return S > p.Smax ? p.Smax : S;
+}
+
+// EARLY (unified scheme only): the first block's loads are issued before the
+// sequence length has arrived, clamped to the chunk's extent in the padded buffer
+// instead of to the last valid key; what they bring in from beyond the valid
+// length is replaced by zeros before use.  Takes the length load off the critical
+// path of a short launch; a padding chunk then reads one block for nothing, so
+// large ragged launches leave it off.
+template <int C, int NW, int UP, bool SYNC, int XN, bool EARLY = false>
+__device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds, int *len_out = nullptr)
+{
+    static_assert(!(EARLY && SYNC), "early loads belong to the unified scheme");
     static_assert(!SYNC || XN >= C, "the synchronized scheme keeps the chunk's logits in LDS");
     constexpr int NG = C / (4 * NW);           // groups of 4 keys each wavefront handles
     static_assert(NG >= 1 && NG % UP == 0, "chunk, wavefront count and stage depth must divide");
@@ -147,12 +184,33 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     const int b = row / p.Hq;
     const int hq = row - b * p.Hq;
     const int hkv = hq / p.G;
-    const int S = valid_len(p, b);
+    int S_raw = 0;
+    if constexpr (EARLY) S_raw = seq_len_issue(p, b);
     const int start = c * C;
-    const int nvalid = min(C, S - start);      // <= 0: no valid key in this chunk
     const size_t slot = (size_t)row * p.nc + c;
 
-    if (nvalid <= 0) {                         // empty chunk: zero partials, no flag
+    const u32x4 qv = reinterpret_cast<const u32x4 *>(p.q + (size_t)row * kHeadDim)[seg];
+    const size_t kv_off = (((size_t)b * p.Hkv + hkv) * p.Smax + start) * kHeadDim;
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + seg;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + seg;
+    // key handled by this lane in group g of the chunk: the NW wavefronts interleave
+    auto key_of = [&](int g) { return (g * NW + wave) * 4 + sub; };
+    u32x4 kA[UP], vA[UP];
+    if constexpr (EARLY) {
+        const int cap = min(C, p.Smax - start) - 1;   // the chunk's last key inside the buffer (start < Smax)
+#pragma unroll
+        for (int u = 0; u < UP; ++u) kA[u] = load_stream(kp + (size_t)min(key_of(u), cap) * 16);
+#pragma unroll
+        for (int u = 0; u < UP; ++u) vA[u] = load_stream(vp + (size_t)min(key_of(u), cap) * 16);
+    }
+
+    if constexpr (EARLY) __builtin_amdgcn_sched_barrier(0);   // the loads above go out before the length is awaited
+    const int S = EARLY ? seq_len_finish(p, S_raw) : valid_len(p, b);
+    if (len_out) *len_out = S;
+    const int nvalid = min(C, S - start);      // <= 0: no valid key in this chunk
+    // With early loads an empty chunk takes the ordinary path below (no block beyond the
+    // first is touched, every key is masked): a branch here would pull the loads behind it.
+    if (!EARLY && nvalid <= 0) {               // empty chunk: zero partials, no flag
         if (tid < kHeadDim) p.ws.num[slot * kHeadDim + tid] = 0.f;
         if (tid == 0) {
             p.ws.den[slot] = 0.f;
@@ -163,13 +221,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         return false;
     }
 
-    const u32x4 qv = reinterpret_cast<const u32x4 *>(p.q + (size_t)row * kHeadDim)[seg];
-    const size_t kv_off = (((size_t)b * p.Hkv + hkv) * p.Smax + start) * kHeadDim;
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + seg;
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + seg;
     const int last = nvalid - 1;
-    // key handled by this lane in group g of the chunk: the NW wavefronts interleave
-    auto key_of = [&](int g) { return (g * NW + wave) * 4 + sub; };
     // blocks (of UP groups per wavefront) that hold at least one valid key
     const int nblk = min(NBLK, (nvalid + UP * NW * 4 - 1) / (UP * NW * 4));
 
@@ -202,24 +254,50 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
                 axpy8(acc, e, vv[u]);
             }
         };
-        // The steady-state loop issues unconditionally (a load inside a branch
-        // would force a full wait at the join); the last one or two blocks are peeled.
-        u32x4 kA[UP], vA[UP], kB[UP], vB[UP];
-        issue(0, kA, vA);
+        u32x4 kB[UP], vB[UP];
         int blk = 0;
+        if constexpr (EARLY) {
+            // Block 0 is already in flight.  Block 1 goes out before block 0 is touched
+            // (clamped into the chunk even when no key is valid), then the loop keeps two
+            // blocks in flight; loads past the last block re-read the last valid key.
+            if constexpr (NBLK > 1) {
+#pragma unroll
+                for (int u = 0; u < UP; ++u) kB[u] = load_stream(kp + (size_t)max(min(key_of(UP + u), last), 0) * 16);
+#pragma unroll
+                for (int u = 0; u < UP; ++u) vB[u] = load_stream(vp + (size_t)max(min(key_of(UP + u), last), 0) * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < UP; ++u)
+                if (key_of(u) > last) vA[u] = u32x4{0u, 0u, 0u, 0u};   // padding may hold anything
 #pragma unroll 1
-        for (; blk + 2 < nblk; blk += 2) {
-            issue(blk + 1, kB, vB);
+            for (; blk + 2 < nblk; blk += 2) {
+                reduce(blk, kA, vA);
+                issue(blk + 2, kA, vA);
+                reduce(blk + 1, kB, vB);
+                issue(blk + 3, kB, vB);
+            }
             reduce(blk, kA, vA);
-            issue(blk + 2, kA, vA);
-            reduce(blk + 1, kB, vB);
-        }
-        if (blk + 2 == nblk) {
-            issue(blk + 1, kB, vB);
-            reduce(blk, kA, vA);
-            reduce(blk + 1, kB, vB);
+            if constexpr (NBLK > 1) {
+                if (blk + 1 < nblk) reduce(blk + 1, kB, vB);
+            }
         } else {
-            reduce(blk, kA, vA);
+            // The steady-state loop issues unconditionally (a load inside a branch
+            // would force a full wait at the join); the last one or two blocks are peeled.
+            issue(0, kA, vA);
+#pragma unroll 1
+            for (; blk + 2 < nblk; blk += 2) {
+                issue(blk + 1, kB, vB);
+                reduce(blk, kA, vA);
+                issue(blk + 2, kA, vA);
+                reduce(blk + 1, kB, vB);
+            }
+            if (blk + 2 == nblk) {
+                issue(blk + 1, kB, vB);
+                reduce(blk, kA, vA);
+                reduce(blk + 1, kB, vB);
+            } else {
+                reduce(blk, kA, vA);
+            }
         }
         const unsigned long long any_bad = __ballot(bad);
         if (lane == 0) lds.flag[wave] = any_bad != 0ull;

@@ -24,12 +24,14 @@ template <int C> struct Tune {
     static constexpr int UP = NG < 4 ? NG : 4;
 };
 
-template <int C>
+// ELECT: the launch is small enough for the in-kernel hand-over (and for early loads).
+template <int C, bool ELECT>
 __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Problem p)
 {
     constexpr int NW = Tune<C>::NW, UP = Tune<C>::UP;
     __shared__ ChunkLds<NW, C> lds;
     const int tid = threadIdx.x;
+    if constexpr (ELECT) fetch_arguments_now(p);
     // Workgroups are dealt to the 8 XCDs round-robin by index.  All chunks of a row
     // go to the same XCD (row % 8), so the row's counters and partial results stay
     // in one L2 instead of bouncing between eight.  Placement only affects speed:
@@ -37,12 +39,11 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     const int j = blockIdx.x >> 3;
     const int row = (blockIdx.x & 7) + 8 * (j / p.nc), c = j % p.nc;
     if (row >= p.rows) return;
-    const int S = valid_len(p, row / p.Hq);
+    int S;
+    const bool flagged = chunk_body<C, NW, UP, false, C, ELECT>(p, row, c, lds, &S);
     const int nb = (S + C - 1) / C;            // chunks of this row that hold a valid key
-
-    const bool flagged = chunk_body<C, NW, UP, false>(p, row, c, lds);
     if (c >= nb) {                             // padding chunk: zero partials were written
-        if (nb == 0 && c == 0 && p.elect) {    // empty sequence: nobody else owns the row
+        if (nb == 0 && c == 0 && ELECT) {    // empty sequence: nobody else owns the row
             if (tid < kHeadDim) p.out[(size_t)row * kHeadDim + tid] = 0;
             if (tid == 0) p.ws.row_flags[row] = 0;
         }
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
         chunk_body<C, NW, UP, true>(p, row, c, lds);
     }
 
-    if (!p.elect) return;                      // a row-epilogue launch follows
+    if (!ELECT) return;                        // a row-epilogue launch follows
     // Publish this chunk's results (written through by chunk_body), then arrive; the
     // last arrival owns the row and reads the others' results past the caches.
     wait_stores_performed();
@@ -112,7 +113,8 @@ template <int C> struct FusedLauncher {
     {
         const unsigned grid = (unsigned)(8ll * ((p.rows + 7) / 8) * p.nc);
         if (grid == 0) return hipSuccess;
-        return launch(decode_fused_kernel<C>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
+        return p.elect ? launch(decode_fused_kernel<C, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
+                       : launch(decode_fused_kernel<C, false>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
     }
 };
 

@@ -85,6 +85,13 @@ typedef struct { void *ptr; size_t bytes; } fd_workspace;
  * invalid or unsupported.  Pure host function.                                */
 size_t fd_workspace_bytes(const fd_shape *shape);
 
+/* A chunk size (keys per partial vector, Section 3's split of the sequence axis)
+ * suited to this shape on MI355X, one of 64, 128, 256, 512, 1024; shape->chunk is
+ * ignored.  0 if the rest of the shape is invalid or unsupported.  The paper leaves
+ * the split size open; any supported value gives the same result up to rounding.
+ * Pure host function.                                                          */
+int32_t fd_pick_chunk(const fd_shape *shape);
+
 /*
  * Prepare a workspace for fd_decode_attn / fd_decode_attn_gqa: zeroes the
  * per-row arrival tickets (one int32 per row) those calls use to elect the

@@ -152,6 +152,41 @@ size_t fd_workspace_bytes(const fd_shape *shape)
     return plan(shape, &L) == FD_OK ? L.total : 0;
 }
 
+// Chunk size from the shape alone (shape->chunk is ignored).  Fitted to sweeps over
+// 64..1024 keys on MI355X: one workgroup streams one chunk, so a chunk should be as
+// long as possible (fewer partial results, fewer hand-overs) while the launch still
+// covers the 256 CUs -- and, when sequences of a batch may differ in length, while
+// there are enough workgroups per CU (about 16) to even out ragged rows.  The
+// grouped kernel has 1/G as many workgroups and a heavier per-workgroup tail; it
+// wants the longest chunk that still gives every CU four of them.
+int32_t fd_pick_chunk(const fd_shape *shape)
+{
+    if (!shape) return 0;
+    fd_shape sh = *shape;
+    sh.chunk = 64;
+    Layout L;
+    if (plan(&sh, &L) != FD_OK) return 0;
+    static const int32_t sizes[] = {1024, 512, 256, 128, 64};
+    const bool grouped = sh.n_q_heads != sh.n_kv_heads;
+    const long long units = (long long)sh.batch * (grouped ? sh.n_kv_heads : sh.n_q_heads);
+    auto workgroups = [&](int32_t c) { return units * (((long long)sh.max_seq + c - 1) / c); };
+    auto largest_with = [&](long long want) -> int32_t {
+        for (int32_t c : sizes)
+            if (workgroups(c) >= want) return c;
+        return 0;
+    };
+    int32_t c = 0;
+    if (grouped) {
+        c = largest_with(1024);
+    } else if (workgroups(1024) >= 4096) {
+        c = 1024;
+    } else if (sh.batch > 1) {
+        c = largest_with(4096);
+    }
+    if (!c) c = largest_with(256);
+    return c ? c : 64;
+}
+
 // The chunk kernel of fd_decode_attn / fd_decode_attn_gqa alone: no election, no
 // row epilogue.
 static fd_status partial_only(const fd_shape *shape, const void *q, const void *k_cache,

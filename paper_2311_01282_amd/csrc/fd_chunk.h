@@ -14,6 +14,8 @@
 // cross-wavefront reduction.
 #pragma once
 
+#include <type_traits>
+
 #include "fd_internal.h"
 
 namespace fd {
@@ -395,7 +397,6 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
 template <int NW, bool COHERENT, typename NbFn>
 __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_load, NbFn nb_fn, float *scratch)
 {
-    constexpr int UB = 4;                       // chunks per thread and batch (32 per batch over the 8 slices)
     auto ld16 = [](const void *ptr) {
         if constexpr (COHERENT) {
             const unsigned long long *w = static_cast<const unsigned long long *>(ptr);
@@ -407,51 +408,81 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_lo
     };
     const int tid = threadIdx.x;
     const int slice = (tid >> 5) & 7, t4 = tid & 31;
-    const bool worker = tid < 256;
+    const bool worker = NW * 64 <= 256 || tid < 256;
     const size_t r0 = (size_t)row * p.nc;
     const float *num = p.ws.num + r0 * kHeadDim + 4 * t4;
     const SlotMeta *meta = p.ws.meta + r0;
 
-    u32x4 nv[UB], mv[UB];
-    auto issue = [&](int c0) {
-#pragma unroll
-        for (int i = 0; i < UB; ++i) {
-            const int c = c0 + 8 * i + slice;
-            const bool on = worker && c < n_load;
-            nv[i] = on ? ld16(num + (size_t)c * kHeadDim) : u32x4{0u, 0u, 0u, 0u};
-            mv[i] = on ? ld16(meta + c) : u32x4{0u, 0u, 0u, 0u};
-        }
-    };
-    issue(0);
-    const int nb = nb_fn();                     // may be a load of its own, in flight with the batch
+    // Within a batch the loads are unconditional and clamped to the last loaded slot (a load
+    // inside a divergent branch would force a full wait where the branch rejoins); slots
+    // outside the row are masked in the arithmetic.  The batch is sized to the row -- 1, 2 or
+    // 4 chunks per thread -- and rows of more than 32 chunks keep two batches in flight.
     float m = -INFINITY, l = 0.f;
     float s[4] = {0.f, 0.f, 0.f, 0.f};
     int f = 0;
-    for (int c0 = 0; c0 < n_load; c0 += 8 * UB) {
-        if (c0) issue(c0);
-        float r[UB], bm = -INFINITY;
+    int nb = 0;
+    if (worker) {
+        const int cap = max(n_load - 1, 0);
+        auto issue = [&](int c0, auto &nv, auto &mv, auto n) {
 #pragma unroll
-        for (int i = 0; i < UB; ++i) {
-            const bool in_row = c0 + 8 * i + slice < nb;
-            r[i] = in_row ? as_f32(mv[i][1]) : -INFINITY;
-            bm = fmaxf(bm, r[i]);
-            f |= in_row ? (int)mv[i][2] : 0;
+            for (int i = 0; i < decltype(n)::value; ++i) {
+                const int c = min(c0 + 8 * i + slice, cap);
+                nv[i] = ld16(num + (size_t)c * kHeadDim);
+                mv[i] = ld16(meta + c);
+            }
+        };
+        auto process = [&](int c0, const auto &nv, const auto &mv, auto n) {
+            constexpr int N = decltype(n)::value;
+            float r[N], bm = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                const bool in_row = c0 + 8 * i + slice < nb;
+                r[i] = in_row ? as_f32(mv[i][1]) : -INFINITY;
+                bm = fmaxf(bm, r[i]);
+                f |= in_row ? (int)mv[i][2] : 0;
+            }
+            if (bm > m) {                       // rescale what was summed so far (never for unflagged rows)
+                const float a = __builtin_amdgcn_exp2f((m - bm) * kLog2e);   // 0 on the first batch
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] *= a;
+                l *= a;
+                m = bm;
+            }
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                // exactly 1 when r_c == m; 0 for slots outside the row (their sums are finite)
+                const float a = r[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((r[i] - m) * kLog2e);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] = __builtin_fmaf(a, as_f32(nv[i][e]), s[e]);
+                l = __builtin_fmaf(a, as_f32(mv[i][0]), l);
+            }
+        };
+        auto single = [&](auto n) {             // the whole row in one batch of N chunks per thread
+            u32x4 nv[decltype(n)::value], mv[decltype(n)::value];
+            issue(0, nv, mv, n);
+            nb = nb_fn();                       // may be a load of its own, in flight with the batch
+            process(0, nv, mv, n);
+        };
+        if (n_load <= 8) {
+            single(std::integral_constant<int, 1>{});
+        } else if (n_load <= 16) {
+            single(std::integral_constant<int, 2>{});
+        } else if (n_load <= 32) {
+            single(std::integral_constant<int, 4>{});
+        } else {
+            constexpr std::integral_constant<int, 4> n{};
+            u32x4 nA[4], mA[4], nB[4], mB[4];
+            issue(0, nA, mA, n);
+            nb = nb_fn();
+            for (int c0 = 0; c0 < n_load; c0 += 64) {
+                issue(c0 + 32, nB, mB, n);
+                process(c0, nA, mA, n);
+                issue(c0 + 64, nA, mA, n);
+                if (c0 + 32 < n_load) process(c0 + 32, nB, mB, n);
+            }
         }
-        if (bm > m) {                           // rescale what was summed so far (never for unflagged rows)
-            const float a = __builtin_amdgcn_exp2f((m - bm) * kLog2e);   // 0 on the first batch
-#pragma unroll
-            for (int e = 0; e < 4; ++e) s[e] *= a;
-            l *= a;
-            m = bm;
-        }
-#pragma unroll
-        for (int i = 0; i < UB; ++i) {
-            // exactly 1 when r_c == m; 0 for slots outside the row (their sums are finite)
-            const float a = r[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((r[i] - m) * kLog2e);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) s[e] = __builtin_fmaf(a, as_f32(nv[i][e]), s[e]);
-            l = __builtin_fmaf(a, as_f32(mv[i][0]), l);
-        }
+    } else {
+        nb = nb_fn();
     }
     // merge the 8 slices (slice order), divide, round to fp16
     float *S = scratch, *L = scratch + 8 * kHeadDim, *M = L + 8;
@@ -481,6 +512,82 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_lo
         *reinterpret_cast<uint2 *>(p.out + (size_t)row * kHeadDim + 4 * tid) = h;
     }
     if (tid == 0) p.ws.row_flags[row] = rf ? 1 : 0;
+}
+
+// The row epilogue for the G <= 16 rows of one head group at once, by 256 threads:
+// thread (h, t) = (tid / 32, tid % 32) owns elements 4t..4t+3 of row row0 + h and walks
+// that row's nb partial results in chunk order with a running maximum of the
+// references (Eq. 2; every factor is exactly 1 for an unflagged row, which makes it
+// the plain sum of Eq. 4).  No thread needs another's data: one memory round trip
+// per 4 chunks, two batches in flight, no LDS and no barrier.  Loads pass the caches
+// (the partial results come from other workgroups of the same launch).
+__device__ __forceinline__ void group_epilogue(const Problem &p, int row0, int G, int nb)
+{
+    const int tid = threadIdx.x, t4 = tid & 31;
+    auto ld16 = [](const void *ptr) {
+        const unsigned long long *w = static_cast<const unsigned long long *>(ptr);
+        const unsigned long long a = load_coherent(&w[0]), b = load_coherent(&w[1]);
+        return u32x4{(unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32)};
+    };
+    for (int h = tid >> 5; h < G; h += 8) {
+        const int row = row0 + h;
+        const size_t r0 = (size_t)row * p.nc;
+        const float *num = p.ws.num + r0 * kHeadDim + 4 * t4;
+        const SlotMeta *meta = p.ws.meta + r0;
+        const int cap = nb - 1;                 // nb >= 1: the caller holds one of the row's chunks
+        float m = -INFINITY, l = 0.f;
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        int f = 0;
+        auto issue = [&](int c0, u32x4 (&nv)[4], u32x4 (&mv)[4]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int c = min(c0 + i, cap);
+                nv[i] = ld16(num + (size_t)c * kHeadDim);
+                mv[i] = ld16(meta + c);
+            }
+        };
+        auto process = [&](int c0, const u32x4 (&nv)[4], const u32x4 (&mv)[4]) {
+            float r[4], bm = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool in_row = c0 + i < nb;
+                r[i] = in_row ? as_f32(mv[i][1]) : -INFINITY;
+                bm = fmaxf(bm, r[i]);
+                f |= in_row ? (int)mv[i][2] : 0;
+            }
+            if (bm > m) {
+                const float a = __builtin_amdgcn_exp2f((m - bm) * kLog2e);   // 0 on the first batch
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] *= a;
+                l *= a;
+                m = bm;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = r[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((r[i] - m) * kLog2e);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s[e] = __builtin_fmaf(a, as_f32(nv[i][e]), s[e]);
+                l = __builtin_fmaf(a, as_f32(mv[i][0]), l);
+            }
+        };
+        u32x4 nA[4], mA[4], nB[4], mB[4];
+        issue(0, nA, mA);
+        if (nb <= 4) {
+            process(0, nA, mA);
+        } else {
+            for (int c0 = 0; c0 < nb; c0 += 8) {
+                issue(c0 + 4, nB, mB);
+                process(c0, nA, mA);
+                issue(c0 + 8, nA, mA);
+                if (c0 + 4 < nb) process(c0 + 4, nB, mB);
+            }
+        }
+        uint2 o;
+        o.x = (unsigned)to_half_bits(s[0] / l) | ((unsigned)to_half_bits(s[1] / l) << 16);
+        o.y = (unsigned)to_half_bits(s[2] / l) | ((unsigned)to_half_bits(s[3] / l) << 16);
+        *reinterpret_cast<uint2 *>(p.out + (size_t)row * kHeadDim + 4 * t4) = o;
+        if (t4 == 0) p.ws.row_flags[row] = f ? 1 : 0;
+    }
 }
 
 // Elects the workgroup that completes a row: a radix-8 tree of arrival counters

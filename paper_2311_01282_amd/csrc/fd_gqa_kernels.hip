@@ -260,10 +260,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     if (tid == 0) lds.last = arrive_and_elect(p, row0, c, nb);
     __syncthreads();
     if (!lds.last) return;
-    for (int h = 0; h < G; ++h) {
-        row_epilogue<4, true>(p, row0 + h, nb, [nb] { return nb; }, lds.tile);
-        __syncthreads();
-    }
+    group_epilogue(p, row0, G, nb);
 }
 
 template <int C> struct GqaLauncher {

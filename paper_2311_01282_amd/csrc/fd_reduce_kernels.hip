@@ -18,6 +18,9 @@ __global__ __launch_bounds__(256) void row_epilogue_kernel(const Problem p)
 {
     __shared__ __attribute__((aligned(16))) float scratch[8 * kHeadDim + 16];
     const int row = blockIdx.x;
+    // one batch of argument loads at the top instead of one per first use
+    asm volatile("" ::"s"(p.ws.num), "s"(p.ws.meta), "s"(p.ws.row_flags), "s"(p.seq_lens), "s"(p.out), "s"(p.nc),
+                 "s"(p.Hq), "s"(p.C), "s"(p.Smax));
     // every slot of the row holds defined values, so the loads need not wait for the length
     row_epilogue<4, false>(p, row, p.nc, [&] { return (valid_len(p, row / p.Hq) + p.C - 1) / p.C; }, scratch);
 }

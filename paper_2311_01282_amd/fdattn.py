@@ -49,6 +49,8 @@ _vp, _f = ctypes.c_void_p, ctypes.c_float
 _sp = ctypes.POINTER(Shape)
 _lib.fd_workspace_bytes.restype = ctypes.c_size_t
 _lib.fd_workspace_bytes.argtypes = [_sp]
+_lib.fd_pick_chunk.restype = ctypes.c_int32
+_lib.fd_pick_chunk.argtypes = [_sp]
 _lib.fd_status_str.restype = ctypes.c_char_p
 _lib.fd_status_str.argtypes = [ctypes.c_int]
 for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel"):
@@ -71,7 +73,7 @@ _lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
 _lib.fd_probe_stream_read.restype = ctypes.c_int
 _lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 
-EXPORTS = ("fd_workspace_bytes", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+EXPORTS = ("fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
@@ -93,6 +95,10 @@ def make_shape(batch, n_q_heads, n_kv_heads, head_dim, max_seq, chunk, scale):
 
 def fd_workspace_bytes(shape):
     return int(_lib.fd_workspace_bytes(ctypes.byref(shape)))
+
+
+def fd_pick_chunk(shape):
+    return int(_lib.fd_pick_chunk(ctypes.byref(shape)))
 
 
 def fd_decode_attn(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):

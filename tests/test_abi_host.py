@@ -125,3 +125,34 @@ def test_status_strings_and_getters(fdattn):
     assert num == base and all(a % 256 == 0 for a in addrs)
     with pytest.raises(fdattn.FdError):
         fdattn.fd_get_flags(sh, base, 16)
+
+
+def test_pick_chunk_is_a_supported_size_and_ignores_the_chunk_field(fdattn):
+    from paper_2311_01282_amd import synth
+    for name, cfg in synth.CONFIGS.items():
+        picks = set()
+        for chunk in (0, 64, 256, 1000):
+            sh = fdattn.make_shape(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"], chunk, 0.1)
+            picks.add(fdattn.fd_pick_chunk(sh))
+        assert len(picks) == 1, name
+        c = picks.pop()
+        assert c in (64, 128, 256, 512, 1024), name
+        # the picked size is accepted by the sizing call
+        assert fdattn.fd_workspace_bytes(fdattn.make_shape(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"], c, 0.1)) > 0
+
+
+def test_pick_chunk_fills_the_chip_when_the_shape_allows_it(fdattn):
+    # one workgroup per (row or head group, chunk): at least 256 of them when any supported size gives that many
+    for (B, Hq, Hkv, Smax) in [(1, 32, 32, 1024), (1, 32, 32, 8192), (16, 32, 32, 4096), (32, 64, 8, 4096),
+                               (4, 32, 32, 32768), (1, 8, 8, 300), (1, 1, 1, 64), (3, 40, 40, 5000)]:
+        c = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, 0.1))
+        units = B * (Hkv if Hq != Hkv else Hq)
+        wgs = lambda cc: units * (-(-Smax // cc))
+        assert c in (64, 128, 256, 512, 1024)
+        if wgs(64) >= 256:
+            assert wgs(c) >= 256, (B, Hq, Hkv, Smax, c)
+        else:
+            assert c == 64
+    # invalid shapes give 0
+    assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0
+    assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0

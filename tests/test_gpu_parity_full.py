@@ -16,7 +16,15 @@ def H():
     return fd_harness
 
 
+def picked(name):
+    """The chunk size bench.py times this workload with."""
+    from paper_2311_01282_amd import fdattn
+    c = synth.CONFIGS[name]
+    return fdattn.fd_pick_chunk(fdattn.make_shape(c["B"], c["Hq"], c["Hkv"], c["D"], c["Smax"], 0, 1.0))
+
+
 def check(oracle, H, name, entry, chunks, poison=False):
+    chunks = sorted(set(chunks) | {picked(name)})
     case = synth.make_config(name, poison_padding=poison)
     want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=16)
     for chunk in chunks:

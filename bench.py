@@ -236,6 +236,17 @@ def main():
         if not grouped:
             rm = Runner(chunk, "fd_decode_attn_multikernel")
             extras["multikernel_chain_us"] = round(wall(rm.step, short, 10) * 1e6, 2)
+        # statistics pass of the calibration (reads K only): histogram of the scaled logits
+        n_bins = 256
+        hist = torch.zeros(n_bins + 2, dtype=torch.int64, device=dev)
+        def stats(i):
+            l = i % layers
+            fdattn.fd_logit_histogram(run.shape, qs[l].data_ptr(), ks[l].data_ptr(), seq_lens.data_ptr(), -16.0, 0.125,
+                                      n_bins, hist.data_ptr(), None, stream)
+        t_stats = wall(stats, short, 10)
+        extras["logit_histogram"] = {"us": round(t_stats * 1e6, 2), "k_bytes": kv_bytes // 2,
+                                     "k_gbs": round(kv_bytes / 2 / t_stats / 1e9, 1),
+                                     "note": "K read once per query head; with grouped heads the repeats hit in L2"}
         # cache-resident figure: the same KV set every call (fits the last-level cache at c0 and c1)
         extras["hot_cache_us"] = round(wall(lambda i: run.step(0), short, 10) * 1e6, 2)
         if planted:

@@ -221,6 +221,60 @@ fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
                           const float **num, const float **den);
 
 /*
+ * Statistics of the softmax inputs (Section 3, the distribution of x_i that the
+ * unified scaling factor is chosen from).  Enqueues a pass over q and k_cache that
+ * ADDS, for every valid key j of every row, the scaled logit x = scale * <q, k_j> to
+ * a histogram of `n_bins` (1..4096) bins of width `bin_width` starting at `x_min`:
+ *   hist[0]            x <  x_min
+ *   hist[1 + i]        x_min + i * bin_width <= x < x_min + (i + 1) * bin_width
+ *   hist[n_bins + 1]   x >= x_min + n_bins * bin_width, or x is NaN
+ * `hist` is device memory, n_bins + 2 uint64, 8-byte aligned, caller-owned; the
+ * caller zeroes it once and may accumulate several calls (layers, prompts) in it.
+ * `min_max` (device, 2 floats, may be NULL) receives min(min_max[0], smallest x)
+ * and max(min_max[1], largest x), NaN excluded; initialise it to {+inf, -inf}.
+ * shape->chunk is ignored; v_cache and a workspace are not needed.  Logits are
+ * evaluated in fp32: one within rounding distance of a bin edge may be counted on
+ * either side of it.  Errors as for fd_decode_attn, plus FD_ERR_BOUNDS for a
+ * non-finite window or bin_width <= 0 and FD_ERR_UNSUPPORTED for n_bins.
+ */
+fd_status fd_logit_histogram(const fd_shape *shape, const void *q, const void *k_cache,
+                             const int32_t *seq_lens, float x_min, float bin_width, int32_t n_bins,
+                             uint64_t *hist, float *min_max, void *stream);
+
+/* What fd_calibrate decides. */
+typedef struct {
+    int32_t   apply;     /* 1: use the unified factor with phi and bounds below;
+                            0: the range is too wide for float32 (the paper's OPT-6.7B
+                            case), the window cut off too much, or nothing was counted:
+                            use fd_decode_attn_sync                                  */
+    float     phi;       /* unified scaling factor                                   */
+    fd_bounds bounds;    /* (x_lo - phi, x_hi - phi), for the guard on x - phi       */
+    float     x_lo, x_hi;/* the chosen range of the logit itself                     */
+    double    covered;   /* fraction of the counted logits inside [x_lo, x_hi) before
+                            widening by margin                                       */
+} fd_calibration;
+
+/*
+ * Choose phi and the bounds from a histogram that fd_logit_histogram filled
+ * (Section 3: more than a fraction `coverage` -- the paper uses 99.99 % -- of the
+ * x_i lie in a range (a, b); when e^{b-a} is representable in float32 the unified
+ * factor is phi = a; when the range is too wide the technique is not applied).
+ * Pure HOST function: `hist` is a host copy, n_bins + 2 values.
+ *   range        the narrowest run of whole bins that leaves at most
+ *                floor((1 - coverage) * total / 2) logits on either side (the two
+ *                outlier slots count as outside), widened by `margin` >= 0 per side;
+ *   phi          x_lo + phi_position * (x_hi - x_lo); phi_position = 0 is the
+ *                paper's phi = a, 1 puts phi at the upper end;
+ *   apply        e^{x_hi - x_lo} * max_seq * 65504 (the largest fp16 magnitude a V
+ *                entry can have) <= FLT_MAX, i.e. no partial sum can overflow.
+ * FD_ERR_NULL, FD_ERR_SHAPE (n_bins, max_seq < 1), FD_ERR_BOUNDS (window, coverage
+ * outside (0, 1], margin < 0, phi_position outside [0, 1]).
+ */
+fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float bin_width,
+                       double coverage, float margin, float phi_position, int32_t max_seq,
+                       fd_calibration *out);
+
+/*
  * Measurement aid, not part of the method: enqueue a plain streaming read of two
  * device buffers of `bytes_each` bytes each (a multiple of 65536) with the same
  * launch geometry as the chunk kernel and no arithmetic.  `sink` is 4 bytes of

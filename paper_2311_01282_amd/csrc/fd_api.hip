@@ -2,6 +2,7 @@
 #include "../../include/fdattn.h"
 #include "fd_internal.h"
 
+#include <cfloat>
 #include <cmath>
 #include <cstdlib>
 
@@ -337,6 +338,84 @@ fd_status fd_get_partials(const fd_shape *shape, fd_workspace ws,
     const fd::WsView w = view(L, ws);
     if (num) *num = w.num;
     if (den) *den = w.den;
+    return FD_OK;
+}
+
+fd_status fd_logit_histogram(const fd_shape *shape, const void *q, const void *k_cache,
+                             const int32_t *seq_lens, float x_min, float bin_width, int32_t n_bins,
+                             uint64_t *hist, float *min_max, void *stream)
+{
+    if (!shape) return FD_ERR_NULL;
+    fd_shape sh = *shape;
+    sh.chunk = 64;                                   // the split plays no part in the statistics
+    Layout L;
+    fd_status st = plan(&sh, &L);
+    if (st != FD_OK) return st;
+    if (!q || !k_cache || !seq_lens || !hist) return FD_ERR_NULL;
+    if (misaligned(q) || misaligned(k_cache) || ((uintptr_t)seq_lens % 4) != 0 || ((uintptr_t)hist % 8) != 0 ||
+        ((uintptr_t)min_max % 4) != 0)
+        return FD_ERR_SHAPE;
+    if (!std::isfinite(x_min) || !std::isfinite(bin_width) || !(bin_width > 0.f)) return FD_ERR_BOUNDS;
+    if (n_bins < 1 || n_bins > 4096) return FD_ERR_UNSUPPORTED;
+    fd::Problem p{};
+    p.q = static_cast<const uint16_t *>(q);
+    p.k = static_cast<const uint16_t *>(k_cache);
+    p.seq_lens = seq_lens;
+    p.B = sh.batch; p.Hq = sh.n_q_heads; p.Hkv = sh.n_kv_heads; p.G = sh.n_q_heads / sh.n_kv_heads;
+    p.Smax = sh.max_seq; p.rows = (int)L.rows; p.scale = sh.scale;
+    FD_TRY(fd::launch_logit_histogram(p, x_min, bin_width, n_bins, reinterpret_cast<unsigned long long *>(hist),
+                                      min_max, static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
+// Host-side choice of phi and the bounds from a histogram (Section 3: the range that
+// holds more than a given fraction of the x_i; phi = a when e^{b-a} fits float32; no
+// unified factor when the range is too wide).
+fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float bin_width, double coverage,
+                       float margin, float phi_position, int32_t max_seq, fd_calibration *out)
+{
+    if (!hist || !out) return FD_ERR_NULL;
+    if (n_bins < 1 || max_seq < 1) return FD_ERR_SHAPE;
+    if (!std::isfinite(x_min) || !std::isfinite(bin_width) || !(bin_width > 0.f) || !std::isfinite(margin) ||
+        !(margin >= 0.f) || !(coverage > 0.0 && coverage <= 1.0) || !(phi_position >= 0.f && phi_position <= 1.f))
+        return FD_ERR_BOUNDS;
+    *out = fd_calibration{};
+    unsigned long long total = 0;
+    for (int32_t i = 0; i < n_bins + 2; ++i) total += hist[i];
+    if (total == 0) return FD_OK;                    // nothing seen: apply = 0
+    const unsigned long long tail = (unsigned long long)std::floor((1.0 - coverage) * (double)total / 2.0);
+    // walk inwards from both ends while the mass left outside stays within the allowance
+    int32_t e_lo = -1, e_hi = -1;
+    unsigned long long below = hist[0];              // logits under edge 0
+    for (int32_t e = 0; e <= n_bins && below <= tail; ++e) {
+        e_lo = e;
+        if (e < n_bins) below += hist[e + 1];
+    }
+    unsigned long long above = hist[n_bins + 1];     // logits at or over edge n_bins
+    for (int32_t e = n_bins; e >= 0 && above <= tail; --e) {
+        e_hi = e;
+        if (e > 0) above += hist[e];
+    }
+    if (e_lo < 0 || e_hi < 0) return FD_OK;          // the window itself cuts off too much: apply = 0
+    if (e_hi <= e_lo) {                              // all mass inside the allowance: keep one bin
+        e_hi = e_lo + 1 < n_bins ? e_lo + 1 : n_bins;
+        e_lo = e_hi - 1;
+    }
+    const double w = (double)bin_width, x0 = (double)x_min;
+    const double x_lo = x0 + e_lo * w - (double)margin, x_hi = x0 + e_hi * w + (double)margin;
+    const double range = x_hi - x_lo;
+    // e^{range} x the longest sequence x the largest fp16 magnitude of V must fit float32
+    const double limit = std::log((double)FLT_MAX) - std::log((double)max_seq) - std::log(65504.0);
+    const double phi = x_lo + (double)phi_position * range;
+    unsigned long long inside = 0;
+    for (int32_t i = e_lo; i < e_hi; ++i) inside += hist[i + 1];
+    out->apply = range <= limit ? 1 : 0;
+    out->phi = (float)phi;
+    out->bounds.lo = (float)(x_lo - phi);
+    out->bounds.hi = (float)(x_hi - phi);
+    out->x_lo = (float)x_lo;
+    out->x_hi = (float)x_hi;
+    out->covered = (double)inside / (double)total;
     return FD_OK;
 }
 

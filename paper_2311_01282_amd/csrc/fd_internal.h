@@ -72,6 +72,9 @@ hipError_t launch_clear_tickets(const Problem &p, hipStream_t s);
 hipError_t launch_row_epilogue(const Problem &p, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
 hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s);
+// fd_stats_kernels.hip : histogram of the scaled logits (uses q, k, seq_lens and the shape only)
+hipError_t launch_logit_histogram(const Problem &p, float x_min, float bin_width, int n_bins,
+                                  unsigned long long *hist, float *min_max, hipStream_t s);
 // fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling
 hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, unsigned *sink, hipStream_t s);
 

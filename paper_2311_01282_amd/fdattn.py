@@ -73,7 +73,18 @@ _lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
 _lib.fd_probe_stream_read.restype = ctypes.c_int
 _lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 
-EXPORTS = ("fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+class Calibration(ctypes.Structure):
+    _fields_ = [("apply", ctypes.c_int32), ("phi", ctypes.c_float), ("bounds", Bounds),
+                ("x_lo", ctypes.c_float), ("x_hi", ctypes.c_float), ("covered", ctypes.c_double)]
+
+
+_lib.fd_logit_histogram.restype = ctypes.c_int
+_lib.fd_logit_histogram.argtypes = [_sp, _vp, _vp, _vp, _f, _f, ctypes.c_int32, _vp, _vp, _vp]
+_lib.fd_calibrate.restype = ctypes.c_int
+_lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _f, _f, ctypes.c_double, _f, _f,
+                              ctypes.c_int32, ctypes.POINTER(Calibration)]
+
+EXPORTS = ("fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
@@ -157,3 +168,18 @@ def fd_get_partials(shape, ws_ptr, ws_bytes):
 
 def fd_probe_stream_read(a, b, bytes_each, sink, stream=0):
     _check(_lib.fd_probe_stream_read(a, b, bytes_each, sink, stream))
+
+
+def fd_logit_histogram(shape, q, k_cache, seq_lens, x_min, bin_width, n_bins, hist, min_max=None, stream=0):
+    """hist / min_max: device pointers (n_bins + 2 uint64 / 2 floats or None)."""
+    _check(_lib.fd_logit_histogram(ctypes.byref(shape), q, k_cache, seq_lens, x_min, bin_width, int(n_bins),
+                                   hist, min_max, stream))
+
+
+def fd_calibrate(hist, n_bins, x_min, bin_width, coverage, margin, phi_position, max_seq):
+    """hist: host sequence of n_bins + 2 counts.  Returns the filled Calibration."""
+    arr = (ctypes.c_uint64 * (n_bins + 2))(*[int(v) for v in hist])
+    out = Calibration()
+    _check(_lib.fd_calibrate(arr, int(n_bins), x_min, bin_width, coverage, margin, phi_position, int(max_seq),
+                             ctypes.byref(out)))
+    return out

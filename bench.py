@@ -269,6 +269,19 @@ def main():
                                   "overhead_pct": round(100.0 * (t_with / t_without - 1.0), 2),
                                   "overhead_one_row_pct": round(100.0 * (t_one / t_without - 1.0), 2)}
 
+    if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
+        # the same step with the cache update fused in: one key fewer in the cache, the step's own
+        # K/V rows attended from their buffers and stored by the same launch (last: it writes the caches)
+        lens_m1 = torch.clamp(seq_lens - 1, min=0)
+        k_new = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+        v_new = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+        def append(i):
+            l = i % layers
+            fdattn.fd_decode_attn_append(run.shape, qs[l].data_ptr(), k_new.data_ptr(), v_new.data_ptr(), ks[l].data_ptr(),
+                                         vs[l].data_ptr(), lens_m1.data_ptr(), phi, bounds, out.data_ptr(),
+                                         run.ws.data_ptr(), run.ws_bytes, stream)
+        extras["fused_append_us"] = round(wall(append, short, 10) * 1e6, 2)
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host threads: whole layer-steps of layer 0, repeated

@@ -143,6 +143,27 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
                              fd_bounds bounds, void *out, fd_workspace ws, void *stream);
 
 /*
+ * One decode step with the cache update fused in (Section 2.2: the step's k and v
+ * are concatenated to the cache before the attention of Eq. 1).  `k_new`, `v_new`
+ * [batch, n_kv_heads, head_dim] fp16 are this step's rows.  For sequence b with
+ * n = clamp(seq_lens[b], 0, max_seq) keys in the cache:
+ *   n < max_seq : out = attention over the n cached keys AND the new one; the new
+ *                 rows are written to k_cache / v_cache at position n.  The rows are
+ *                 taken from k_new / v_new, not read back from the cache.
+ *   n == max_seq: the cache is full; the new rows are dropped and out is the
+ *                 attention over the cached keys alone.
+ * seq_lens is not modified: the caller adds 1 to the lengths it passes to the next
+ * step (and to fd_list_flagged_rows for this one).  Nothing else of the cache is
+ * written.  Grouped shapes (2 <= n_q_heads / n_kv_heads <= 16) take the grouped
+ * kernel, all others the per-row kernel; workspace, flags, recomputation, errors
+ * and the fd_workspace_init requirement are those of fd_decode_attn.  The same
+ * k_cache / v_cache must not be in use by another call in flight.
+ */
+fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void *k_new, const void *v_new,
+                                void *k_cache, void *v_cache, const int32_t *seq_lens, float phi,
+                                fd_bounds bounds, void *out, fd_workspace ws, void *stream);
+
+/*
  * The same method as a chain of five small-step kernels with no atomics at all,
  * following Section 3 to the letter:
  *   1. per (row, chunk): Eq. 4 inner sums and the range guard;

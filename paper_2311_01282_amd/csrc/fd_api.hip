@@ -98,6 +98,8 @@ fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const v
     p->Smax = sh->max_seq; p->C = sh->chunk; p->nc = (int)L.nc; p->rows = (int)L.rows;
     p->scale = sh->scale; p->phi = 0.f; p->lo = 0.f; p->hi = 0.f;
     p->elect = 0;
+    p->k_new = p->v_new = nullptr;
+    p->k_store = p->v_store = nullptr;
     return FD_OK;
 }
 
@@ -262,6 +264,34 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
     // the grouped kernel holds fewer workgroups per CU, so the election hurts it sooner
     p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
     FD_TRY(fd::launch_decode_fused_gqa(p, s));
+    if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
+    return FD_OK;
+}
+
+fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void *k_new, const void *v_new,
+                                void *k_cache, void *v_cache, const int32_t *seq_lens, float phi,
+                                fd_bounds bounds, void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (!k_new || !v_new) return FD_ERR_NULL;
+    if (misaligned(k_new) || misaligned(v_new)) return FD_ERR_SHAPE;
+    if (p.rows == 0) return FD_OK;
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.k_store = static_cast<uint16_t *>(k_cache);
+    p.v_store = static_cast<uint16_t *>(v_cache);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (p.G >= 2 && p.G <= 16) {
+        p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
+        FD_TRY(fd::launch_decode_fused_gqa(p, s));
+    } else {
+        p.elect = elect_in_kernel((long long)p.rows * p.nc);
+        FD_TRY(fd::launch_decode_fused(p, s));
+    }
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;
 }

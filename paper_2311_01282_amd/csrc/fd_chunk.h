@@ -160,9 +160,7 @@ __device__ __forceinline__ int seq_len_issue(const Problem &p, int b)
 }
 __device__ __forceinline__ int seq_len_finish(const Problem &p, int raw)
 {
-    int S = __builtin_amdgcn_readfirstlane(raw);
-    S = S < 0 ? 0 : S;
-    return S > p.Smax ? p.Smax : S;
+    return clamp_len(p, __builtin_amdgcn_readfirstlane(raw));     // resident keys
 }
 
 // EARLY (unified scheme only): the first block's loads are issued before the
@@ -207,9 +205,14 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     }
 
     if constexpr (EARLY) __builtin_amdgcn_sched_barrier(0);   // the loads above go out before the length is awaited
-    const int S = EARLY ? seq_len_finish(p, S_raw) : valid_len(p, b);
+    const int S_res = EARLY ? seq_len_finish(p, S_raw) : clamp_len(p, p.seq_lens[b]);
+    const int S = effective_len(p, S_res);
     if (len_out) *len_out = S;
     const int nvalid = min(C, S - start);      // <= 0: no valid key in this chunk
+    const int nres = min(C, S_res - start);    // of them resident in the cache
+    // A fused append puts the new key at offset jn of exactly one chunk of the row.
+    const int jn = S_res - start;
+    const bool owner = (S != S_res) & (jn >= 0) & (jn < C);
     // With early loads an empty chunk takes the ordinary path below (no block beyond the
     // first is touched, every key is masked): a branch here would pull the loads behind it.
     if (!EARLY && nvalid <= 0) {               // empty chunk: zero partials, no flag
@@ -223,9 +226,12 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         return false;
     }
 
-    const int last = nvalid - 1;
-    // blocks (of UP groups per wavefront) that hold at least one valid key
-    const int nblk = min(NBLK, (nvalid + UP * NW * 4 - 1) / (UP * NW * 4));
+    const int last = nres - 1;                 // last resident key; the appended one is handled apart
+    // blocks (of UP groups per wavefront) that hold at least one resident key
+    const int nblk = min(NBLK, (nres + UP * NW * 4 - 1) / (UP * NW * 4));
+    // the appended rows of this row's KV head
+    const u32x4 *knp = reinterpret_cast<const u32x4 *>(p.k_new + ((size_t)b * p.Hkv + hkv) * kHeadDim) + seg;
+    const u32x4 *vnp = reinterpret_cast<const u32x4 *>(p.v_new + ((size_t)b * p.Hkv + hkv) * kHeadDim) + seg;
 
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float den = 0.f;
@@ -282,7 +288,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
             if constexpr (NBLK > 1) {
                 if (blk + 1 < nblk) reduce(blk + 1, kB, vB);
             }
-        } else {
+        } else if (nres > 0) {                     // (a chunk may hold the appended key only)
             // The steady-state loop issues unconditionally (a load inside a branch
             // would force a full wait at the join); the last one or two blocks are peeled.
             issue(0, kA, vA);
@@ -301,22 +307,47 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
                 reduce(blk, kA, vA);
             }
         }
+        if (owner && wave == 0 && sub == 0) {
+            // The appended key: one more term of Eq. 4, taken from the step's own K/V rows by
+            // the 16 lanes of the first key column, which also put the rows into the cache.
+            const u32x4 kn = *knp, vn = *vnp;
+            const float d = row16_sum(dot8(qv, kn)) * scale + nphi;
+            bad |= !((d > lo) & (d < hi));
+            const float e = __builtin_amdgcn_exp2f(d * kLog2e);
+            den += e;
+            axpy8(acc, e, vn);
+            if (hq == hkv * p.G) {                  // one writer per KV head
+                const size_t at = (((size_t)b * p.Hkv + hkv) * p.Smax + S_res) * kHeadDim;
+                reinterpret_cast<u32x4 *>(p.k_store + at)[seg] = kn;
+                reinterpret_cast<u32x4 *>(p.v_store + at)[seg] = vn;
+            }
+        }
         const unsigned long long any_bad = __ballot(bad);
         if (lane == 0) lds.flag[wave] = any_bad != 0ull;
     } else {
-        // Pass 1: logits of the whole chunk into LDS, and their maximum.
+        // Pass 1: logits of the whole chunk into LDS, and their maximum.  An appended key
+        // takes its place at offset jn with the logit of the step's own K row; loads of
+        // non-resident positions are clamped into the chunk and their values replaced.
         float m = -INFINITY;
         const float scale = p.scale;
+        const int jnew = owner ? jn : -1;
+        u32x4 vn = {0u, 0u, 0u, 0u};
+        float x_new = -INFINITY;
+        if (owner) {
+            x_new = row16_sum(dot8(qv, *knp)) * scale;
+            vn = *vnp;
+        }
+        const int nblk_all = min(NBLK, (nvalid + UP * NW * 4 - 1) / (UP * NW * 4));
 #pragma unroll 1
-        for (int blk = 0; blk < nblk; ++blk) {
+        for (int blk = 0; blk < nblk_all; ++blk) {
             u32x4 kk[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)min(key_of(blk * UP + u), last) * 16);
+            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)max(min(key_of(blk * UP + u), last), 0) * 16);
 #pragma unroll
             for (int u = 0; u < UP; ++u) {
                 const int kidx = key_of(blk * UP + u);
                 float x = row16_sum(dot8(qv, kk[u])) * scale;
-                x = kidx <= last ? x : -INFINITY;
+                x = kidx <= last ? x : (kidx == jnew ? x_new : -INFINITY);
                 if (seg == 0) lds.x[kidx] = x;
                 m = fmaxf(m, x);
             }
@@ -331,16 +362,26 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int w = 1; w < NW; ++w) mc = fmaxf(mc, lds.mx[w]);
         // Pass 2: e^{x - m} and the V products.
 #pragma unroll 1
-        for (int blk = 0; blk < nblk; ++blk) {
+        for (int blk = 0; blk < nblk_all; ++blk) {
             u32x4 vv[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)min(key_of(blk * UP + u), last) * 16);
+            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)max(min(key_of(blk * UP + u), last), 0) * 16);
 #pragma unroll
             for (int u = 0; u < UP; ++u) {
-                const float e = __builtin_amdgcn_exp2f((lds.x[key_of(blk * UP + u)] - mc) * kLog2e);   // 0 for padding
+                const int kidx = key_of(blk * UP + u);
+                const float e = __builtin_amdgcn_exp2f((lds.x[kidx] - mc) * kLog2e);   // 0 for padding
                 den += e;
-                axpy8(acc, e, vv[u]);
+                // the appended V row for its key, and for every key when no resident row was
+                // there to clamp to (weight zero then, but the cache may hold anything)
+                axpy8(acc, e, (kidx == jnew) | (nres <= 0) ? vn : vv[u]);
             }
+        }
+        if (owner && hq == hkv * p.G && wave == 0 && sub == 0 && p.k_store) {
+            // a recomputed chunk of the fused kernels has stored the rows already; the
+            // synchronized entry points come here first
+            const size_t at = (((size_t)b * p.Hkv + hkv) * p.Smax + S_res) * kHeadDim;
+            reinterpret_cast<u32x4 *>(p.k_store + at)[seg] = *knp;
+            reinterpret_cast<u32x4 *>(p.v_store + at)[seg] = vn;
         }
     }
 

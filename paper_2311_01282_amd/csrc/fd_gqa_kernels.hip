@@ -41,6 +41,8 @@ struct GqaLds {
     // then (rarely) the per-row recomputation's workspace: never live together.
     alignas(16) float tile[kTileFloats];
     float den[4][64];
+    float e_new[16];                 // weight of an appended key per head (0 when there is none)
+    int   f_new[16];                 // ... and whether it left the bounds
     unsigned long long bad[4];
     float red[4];
     int last;
@@ -73,10 +75,13 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     if (gi >= groups) return;
     const int b = gi / p.Hkv;
     const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group
-    const int S = valid_len(p, b);
+    const int S_res = clamp_len(p, p.seq_lens[b]);          // keys resident in the cache
+    const int S = effective_len(p, S_res);                  // plus the appended one, if any
     const int nb = (S + C - 1) / C;
     const int start = c * C;
     const int nvalid = min(C, S - start);
+    const int nres = min(C, S_res - start);
+    const bool owner = (S != S_res) & (S_res >= start) & (S_res < start + C);   // this chunk takes the appended key
 
     if (nvalid <= 0) {                         // padding chunk: zero partials, no flag
         for (int i = tid; i < G * kHeadDim; i += kGqaThreads)
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     const size_t kv_off = ((size_t)gi * p.Smax + start) * kHeadDim;
     const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + n;
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + n;
-    const int last = nvalid - 1;
+    const int last = nres - 1;                 // last resident key; the appended one joins at the reduction
     const float nphi = -p.phi, lo = p.lo, hi = p.hi, scale = p.scale;
     u32x4 *kst = reinterpret_cast<u32x4 *>(lds.tile) + wave * 256;     // this wavefront's 16 x 16 slots
 
@@ -167,7 +172,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     };
     // This wavefront's blocks are wave, wave + 4, ...; nmine of them hold a valid key.
     // Two-stage software pipeline, steady state free of branches around loads.
-    const int nblk_valid = min(NBLK, (nvalid + 15) / 16);
+    const int nblk_valid = min(NBLK, (nres + 15) / 16);
     const int nmine = nblk_valid > wave ? (nblk_valid - wave + 3) / 4 : 0;
     if (nmine > 0) {
         u32x4 kA[4], vA[4], kB[4], vB[4];
@@ -192,6 +197,29 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         }
     }
 
+    // ---- the appended key, if this chunk takes it: one more term of Eq. 4 per head ----
+    // Lane group (wave, g) handles head 4 wave + g on the vector ALU: weight e^{x - phi}
+    // and guard from the step's own K row.  The weights go to LDS and enter the sums at
+    // the reduction below, multiplied with the step's V row.
+    float e_new = 0.f;
+    int f_new = 0;
+    if (owner) {
+        const int hh = 4 * wave + g;
+        const size_t at_new = (size_t)gi * kHeadDim;
+        const u32x4 kn = reinterpret_cast<const u32x4 *>(p.k_new + at_new)[n];
+        const u32x4 qh = reinterpret_cast<const u32x4 *>(p.q + (size_t)(row0 + min(hh, G - 1)) * kHeadDim)[n];
+        const float d = row16_sum(dot8(qh, kn)) * scale + nphi;
+        if (hh < G) {
+            f_new = !((d > lo) & (d < hi));
+            e_new = __builtin_amdgcn_exp2f(d * kLog2e);
+        }
+        if (wave == 0 && g == 0) {             // 16 lanes put the rows into the cache
+            const size_t at = ((size_t)gi * p.Smax + S_res) * kHeadDim;
+            reinterpret_cast<u32x4 *>(p.k_store + at)[n] = kn;
+            reinterpret_cast<u32x4 *>(p.v_store + at)[n] = reinterpret_cast<const u32x4 *>(p.v_new + at_new)[n];
+        }
+    }
+
     // ---- workgroup reduction and publication of the G rows' partial results ----
     const unsigned long long bad_mask = __ballot(bad);
     __syncthreads();                           // every wavefront is done with its K staging
@@ -209,6 +237,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     }
     lds.den[wave][lane] = den;
     if (lane == 0) lds.bad[wave] = bad_mask;
+    if (n == 0) { lds.e_new[4 * wave + g] = e_new; lds.f_new[4 * wave + g] = f_new; }
     __syncthreads();
     // 4 consecutive elements per thread: one 16-byte LDS read per wavefront tile, 16 bytes out
     for (int i = 4 * tid; i < G * kHeadDim; i += 4 * kGqaThreads) {
@@ -217,19 +246,29 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         const float4 cc = *reinterpret_cast<const float4 *>(&lds.tile[32 * kHeadDim + i]);
         const float4 d = *reinterpret_cast<const float4 *>(&lds.tile[48 * kHeadDim + i]);
         const int q = i & (kHeadDim - 1);      // LDS position -> element index (see the layout above)
-        float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + 2 * (q & 63) + 4 * (q >> 6)];
+        const int d0 = 2 * (q & 63) + 4 * (q >> 6);
+        float4 o = make_float4(a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y, a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
+        if (owner) {                           // + e_new[head] * v_new[d0 .. d0 + 3]
+            const float en = lds.e_new[i / kHeadDim];
+            const uint2 vn = *reinterpret_cast<const uint2 *>(p.v_new + (size_t)gi * kHeadDim + d0);
+            const half2_t v01 = as_h2(vn.x), v23 = as_h2(vn.y);
+            o.x = __builtin_fmaf(en, (float)v01.x, o.x); o.y = __builtin_fmaf(en, (float)v01.y, o.y);
+            o.z = __builtin_fmaf(en, (float)v23.x, o.z); o.w = __builtin_fmaf(en, (float)v23.y, o.w);
+        }
+        float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + d0];
         if (p.elect) {      // read by another workgroup of this launch: write through
-            store_coherent4(dst, a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y, a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
+            store_coherent4(dst, o.x, o.y, o.z, o.w);
         } else {
-            *reinterpret_cast<float4 *>(dst) = make_float4(a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y,
-                                                           a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
+            *reinterpret_cast<float4 *>(dst) = o;
         }
     }
     const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
     // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
-    const unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
+    unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
+#pragma unroll
+    for (int h = 0; h < 16; ++h) flagged_heads |= (unsigned)(lds.f_new[h] != 0) << h;
     if (tid < G) {
-        float s = 0.f;
+        float s = lds.e_new[tid];
 #pragma unroll
         for (int w = 0; w < 4; ++w)
 #pragma unroll

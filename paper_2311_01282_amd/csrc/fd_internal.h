@@ -41,13 +41,28 @@ struct Problem {
     float scale, phi, lo, hi;
     int elect;     // 1: chunk kernels elect a finisher per row and run the row epilogue themselves;
                    // 0: a separate row-epilogue launch follows (no per-workgroup hand-over latency)
+    // Fused append (null otherwise): this step's K and V rows, [B, Hkv, D].  Sequence b then
+    // has seq_lens[b] resident keys plus the new one at position seq_lens[b] (if the cache
+    // has room); the new rows are taken from here, never from the cache, and are also
+    // written into the cache through k_store / v_store (the cache pointers, writable).
+    const uint16_t *k_new, *v_new;
+    uint16_t *k_store, *v_store;
 };
 
+// Number of keys resident in the cache: the clamped entry of seq_lens.
+__device__ __forceinline__ int clamp_len(const Problem &p, int raw)
+{
+    raw = raw < 0 ? 0 : raw;
+    return raw > p.Smax ? p.Smax : raw;
+}
+// Keys a row attends over: the resident ones plus the appended one, if any and if it fits.
+__device__ __forceinline__ int effective_len(const Problem &p, int resident)
+{
+    return resident + ((p.k_new != nullptr) & (resident < p.Smax));
+}
 __device__ __forceinline__ int valid_len(const Problem &p, int b)
 {
-    int S = p.seq_lens[b];
-    S = S < 0 ? 0 : S;
-    return S > p.Smax ? p.Smax : S;
+    return effective_len(p, clamp_len(p, p.seq_lens[b]));
 }
 
 // Launch that reports its own error code (the runtime's "last error" slot is shared

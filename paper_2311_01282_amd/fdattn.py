@@ -84,7 +84,10 @@ _lib.fd_calibrate.restype = ctypes.c_int
 _lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _f, _f, ctypes.c_double, _f, _f,
                               ctypes.c_int32, ctypes.POINTER(Calibration)]
 
-EXPORTS = ("fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+_lib.fd_decode_attn_append.restype = ctypes.c_int
+_lib.fd_decode_attn_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+
+EXPORTS = ("fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
@@ -183,3 +186,8 @@ def fd_calibrate(hist, n_bins, x_min, bin_width, coverage, margin, phi_position,
     _check(_lib.fd_calibrate(arr, int(n_bins), x_min, bin_width, coverage, margin, phi_position, int(max_seq),
                              ctypes.byref(out)))
     return out
+
+
+def fd_decode_attn_append(shape, q, k_new, v_new, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_append(ctypes.byref(shape), q, k_new, v_new, k_cache, v_cache, seq_lens, phi,
+                                      Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))

@@ -296,6 +296,35 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
                        fd_calibration *out);
 
 /*
+ * Prompt (prefill) phase: the attention of Eq. 1 for every token of a prompt at
+ * once, token i attending to tokens 0..i of its sequence, with the asynchronized
+ * softmax of Section 3 (the paper applies it to both phases): weights against the
+ * unified factor phi, partial sums over disjoint key sets added without a
+ * maximum exchange, the range guard lo < x - phi < hi on every logit that takes
+ * part, and on-the-spot recomputation with the synchronized scheme for a tile of
+ * 64 queries whose guard fired.
+ *   q, out   [batch, n_q_heads, max_seq, head_dim] fp16 (out is written)
+ *   k_cache, v_cache [batch, n_kv_heads, max_seq, head_dim] fp16 (the prompt's keys)
+ *   seq_lens [batch]: prompt length n_b = clamp(seq_lens[b], 0, max_seq); rows
+ *            i >= n_b of out are set to zero, keys >= n_b are never used.
+ * shape->chunk is ignored.  `ws`: device scratch of fd_prefill_workspace_bytes(shape)
+ * bytes, 256-byte aligned, arbitrary previous contents (it receives a transposed
+ * bf16 hi/lo copy of V and one flag byte per (row head, 64-query tile)); no
+ * initialisation call is needed.  Arithmetic: fp16 products with fp32 accumulation
+ * for the scores, fp32 exponentials rounded to bf16 for the weights (the
+ * denominator sums the rounded weights), V exact as bf16 hi + lo.
+ * Errors as for fd_decode_attn; FD_ERR_UNSUPPORTED beyond 65535 heads, sequences
+ * or batch * n_kv_heads.
+ */
+size_t    fd_prefill_workspace_bytes(const fd_shape *shape);
+fd_status fd_prefill_attn(const fd_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *seq_lens, float phi, fd_bounds bounds, void *out,
+                          fd_workspace ws, void *stream);
+/* Device pointer into `ws`: tile_flags [batch, n_q_heads, ceil(max_seq / 64)], 1 where
+ * the guard fired for a logit of that 64-query tile (the tile was recomputed). */
+fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uint8_t **tile_flags);
+
+/*
  * Measurement aid, not part of the method: enqueue a plain streaming read of two
  * device buffers of `bytes_each` bytes each (a multiple of 65536) with the same
  * launch geometry as the chunk kernel and no arithmetic.  `sink` is 4 bytes of

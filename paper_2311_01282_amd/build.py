@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfdattn.so")
 SOURCES = ["fd_api.hip", "fd_row_kernels.hip", "fd_reduce_kernels.hip", "fd_gqa_kernels.hip",
-           "fd_stats_kernels.hip", "fd_probe_kernels.hip"]
+           "fd_stats_kernels.hip", "fd_prefill_kernels.hip", "fd_probe_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed-fp32 VALU forms are kept out of the generated code on purpose

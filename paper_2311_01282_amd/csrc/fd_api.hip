@@ -449,6 +449,76 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
     return FD_OK;
 }
 
+namespace {
+struct PrefillLayout { size_t vt_hi, vt_lo, flags, total; int spad, tiles; };
+fd_status plan_prefill(const fd_shape *shape, PrefillLayout *P)
+{
+    if (!shape) return FD_ERR_NULL;
+    fd_shape sh = *shape;
+    sh.chunk = 64;                                   // the prompt phase has its own tiling
+    Layout L;
+    fd_status st = plan(&sh, &L);
+    if (st != FD_OK) return st;
+    P->spad = (sh.max_seq + 63) / 64 * 64;
+    P->tiles = P->spad / 64;
+    const size_t vt = (size_t)sh.batch * sh.n_kv_heads * fd::kHeadDim * P->spad * sizeof(uint16_t);
+    size_t off = 0;
+    P->vt_hi = off;  off = align_up(off + vt);
+    P->vt_lo = off;  off = align_up(off + vt);
+    P->flags = off;  off = align_up(off + (size_t)sh.batch * sh.n_q_heads * P->tiles);
+    P->total = off;
+    return FD_OK;
+}
+}  // namespace
+
+size_t fd_prefill_workspace_bytes(const fd_shape *shape)
+{
+    PrefillLayout P;
+    return plan_prefill(shape, &P) == FD_OK ? P.total : 0;
+}
+
+fd_status fd_prefill_attn(const fd_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                          const int32_t *seq_lens, float phi, fd_bounds bounds, void *out,
+                          fd_workspace ws, void *stream)
+{
+    PrefillLayout P;
+    fd_status st = plan_prefill(shape, &P);
+    if (st != FD_OK) return st;
+    if (!q || !k_cache || !v_cache || !seq_lens || !out) return FD_ERR_NULL;
+    if (misaligned(q) || misaligned(k_cache) || misaligned(v_cache) || misaligned(out) || ((uintptr_t)seq_lens % 4) != 0)
+        return FD_ERR_SHAPE;
+    if (!std::isfinite(phi) || !std::isfinite(bounds.lo) || !std::isfinite(bounds.hi) || !(bounds.lo < bounds.hi))
+        return FD_ERR_BOUNDS;
+    if (!ws.ptr || ((uintptr_t)ws.ptr % kAlign) != 0 || ws.bytes < P.total) return FD_ERR_WORKSPACE;
+    if (shape->n_q_heads > 65535 || shape->batch > 65535 || (long long)shape->batch * shape->n_kv_heads > 65535)
+        return FD_ERR_UNSUPPORTED;                   // grid dimensions
+    fd::PrefillProblem p{};
+    char *base = static_cast<char *>(ws.ptr);
+    p.q = static_cast<const uint16_t *>(q);
+    p.k = static_cast<const uint16_t *>(k_cache);
+    p.v = static_cast<const uint16_t *>(v_cache);
+    p.seq_lens = seq_lens;
+    p.out = static_cast<uint16_t *>(out);
+    p.vt_hi = reinterpret_cast<uint16_t *>(base + P.vt_hi);
+    p.vt_lo = reinterpret_cast<uint16_t *>(base + P.vt_lo);
+    p.tile_flags = reinterpret_cast<uint8_t *>(base + P.flags);
+    p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.G = p.Hq / p.Hkv;
+    p.Smax = shape->max_seq; p.Spad = P.spad; p.tiles = P.tiles;
+    p.scale = shape->scale; p.phi = phi; p.lo = bounds.lo; p.hi = bounds.hi;
+    FD_TRY(fd::launch_prefill(p, static_cast<hipStream_t>(stream)));
+    return FD_OK;
+}
+
+fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uint8_t **tile_flags)
+{
+    PrefillLayout P;
+    fd_status st = plan_prefill(shape, &P);
+    if (st != FD_OK) return st;
+    if (!ws.ptr || ((uintptr_t)ws.ptr % kAlign) != 0 || ws.bytes < P.total) return FD_ERR_WORKSPACE;
+    if (tile_flags) *tile_flags = reinterpret_cast<const uint8_t *>(static_cast<char *>(ws.ptr) + P.flags);
+    return FD_OK;
+}
+
 fd_status fd_probe_stream_read(const void *a, const void *b, size_t bytes_each,
                                void *sink, void *stream)
 {

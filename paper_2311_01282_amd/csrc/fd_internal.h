@@ -90,6 +90,17 @@ hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s);
 // fd_stats_kernels.hip : histogram of the scaled logits (uses q, k, seq_lens and the shape only)
 hipError_t launch_logit_histogram(const Problem &p, float x_min, float bin_width, int n_bins,
                                   unsigned long long *hist, float *min_max, hipStream_t s);
+// fd_prefill_kernels.hip : prompt phase (causal attention of all prompt tokens at once)
+struct PrefillProblem {
+    const uint16_t *q, *k, *v;   // q [B, Hq, Smax, D]; k, v [B, Hkv, Smax, D]
+    const int32_t *seq_lens;
+    uint16_t *out;               // [B, Hq, Smax, D]
+    uint16_t *vt_hi, *vt_lo;     // workspace: V transposed, [B, Hkv, D, Spad] bf16 bit patterns, hi + lo = V
+    uint8_t *tile_flags;         // workspace: [B, Hq, tiles]
+    int B, Hq, Hkv, G, Smax, Spad, tiles;   // Spad = Smax rounded up to 64; tiles = Spad / 64
+    float scale, phi, lo, hi;
+};
+hipError_t launch_prefill(const PrefillProblem &p, hipStream_t s);
 // fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling
 hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, unsigned *sink, hipStream_t s);
 

@@ -1,0 +1,363 @@
+// Prompt (prefill) phase with the asynchronized softmax of Section 3: every token of a
+// prompt attends to itself and the tokens before it (Eq. 1 under the causal mask), all
+// weights taken against the unified scaling factor phi, so that partial sums over
+// disjoint key sets simply add (Eq. 4) -- here across the four wavefronts of a
+// workgroup, which split the keys of a 64-query tile between them and never exchange a
+// maximum.  A tile whose guard fires is redone on the spot with the synchronized
+// scheme (running maximum per query, Eq. 2 to merge the wavefronts).
+//
+// Matrix-core mapping (16x16x32 MFMA; lane = (n, g) = (lane % 16, lane / 16)):
+//   scores   S^T[key][query] = K . Q^T      A = 16 keys of K straight from global memory
+//            (lane (n, g) fetches bytes 64 kb + 16 g .. +15 of its key's row), B = Q^T held
+//            in registers for the whole kernel.  Row 4g + r of key block t is key
+//            k0 + 8g + 4t + r: with that permutation the two score tiles of a 32-key
+//            step leave lane (n, g) holding keys k0 + 8g .. 8g + 7 of query n -- exactly
+//            the B operand of the second product, no data movement.
+//   weights  P = e^{s S^T - phi}, fp32, guard, causal mask.  fp16 cannot hold e^{x - phi}
+//            over the admissible range and bf16 has 8 significant bits, so P goes to the
+//            matrix cores as bf16 hi + lo (16 bits); the denominator sums hi + lo, the
+//            weight the products see.
+//   output   O^T[d][query] = V^T . P^T       A = V^T from a transposed copy of V that a
+//            small pass writes first (keys contiguous per d: 16 bytes per lane, no LDS, no
+//            transposition in the loop), likewise split into bf16 hi + lo whose sum is the
+//            fp16 value exactly.  Three MFMAs per tile (Vh Ph + Vl Ph + Vh Pl) buy
+//            fp16-grade results from bf16 matrix cores.
+// No LDS and no barrier inside the key loop; LDS only carries the final sum over the
+// wavefronts.
+#include "fd_chunk.h"
+
+namespace fd {
+
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kQTile = 64;       // query rows per workgroup
+constexpr int kStep = 32;        // keys per wavefront step
+
+// fp32 -> bf16 bit pattern, round to nearest even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ unsigned bf16_bits(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    if (x != x) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf16_value(unsigned bits) { return __builtin_bit_cast(float, bits << 16); }
+
+// ---- pass 0: V [B,Hkv,Smax,D] fp16 -> V^T hi/lo [B,Hkv,D,Spad] bf16, zero beyond the prompt ----
+__global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p)
+{
+    __shared__ float tile[64][kHeadDim + 1];
+    const int gi = blockIdx.y;                          // (sequence, KV head)
+    const int b = gi / p.Hkv;
+    const int k0 = blockIdx.x * 64;
+    int S = p.seq_lens[b];
+    S = S < 0 ? 0 : (S > p.Smax ? p.Smax : S);
+    const int tid = threadIdx.x;
+    // 64 keys x 128 d: thread reads 8 d of one key (16 bytes), 4 times
+    for (int i = tid; i < 64 * 16; i += 256) {
+        const int key = i >> 4, c = i & 15;
+        float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (k0 + key < S) {
+            const u32x4 w = *reinterpret_cast<const u32x4 *>(p.v + ((size_t)gi * p.Smax + k0 + key) * kHeadDim + 8 * c);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const half2_t h = as_h2(w[j]);
+                f[2 * j] = (float)h.x;
+                f[2 * j + 1] = (float)h.y;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tile[key][8 * c + j] = f[j];
+    }
+    __syncthreads();
+    // thread writes 8 keys of one d (16 bytes) to each of hi and lo, 4 times
+    for (int i = tid; i < kHeadDim * 8; i += 256) {
+        const int d = i >> 3, kc = i & 7;
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            unsigned h2[2], l2[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float x = tile[8 * kc + 2 * j + e][d];
+                h2[e] = bf16_bits(x);
+                l2[e] = bf16_bits(x - bf16_value(h2[e]));         // exact difference; fp16 = hi + lo exactly
+            }
+            hi[j] = h2[0] | (h2[1] << 16);
+            lo[j] = l2[0] | (l2[1] << 16);
+        }
+        const size_t at = ((size_t)gi * kHeadDim + d) * p.Spad + k0 + 8 * kc;
+        *reinterpret_cast<u32x4 *>(p.vt_hi + at) = u32x4{hi[0], hi[1], hi[2], hi[3]};
+        *reinterpret_cast<u32x4 *>(p.vt_lo + at) = u32x4{lo[0], lo[1], lo[2], lo[3]};
+    }
+}
+
+struct PrefillLds {
+    float buf[2][128][64];       // two wavefronts' accumulators, [register][lane]
+    float den[4][4][64];         // [wave][query block][lane]
+    float mx[4][4][64];
+    int bad[4];
+};
+
+// One pass over the keys of a query tile by one wavefront.  ONLINE: running maximum.
+template <bool ONLINE>
+__device__ __forceinline__ void tile_pass(const PrefillProblem &p, int b, int hq, int i0, int S, int wave, int lane,
+                                          f32x4 (&acc)[8][4], float (&den)[4], float (&mrun)[4], bool &bad)
+{
+    const int n = lane & 15, g = lane >> 4;
+    const int hkv = hq / p.G;
+    const size_t kv_head = (size_t)b * p.Hkv + hkv;
+    const uint16_t *qbase = p.q + (((size_t)b * p.Hq + hq) * p.Smax) * kHeadDim;
+    const uint16_t *kbase = p.k + kv_head * p.Smax * kHeadDim;
+    const uint16_t *vh = p.vt_hi + kv_head * kHeadDim * p.Spad;
+    const uint16_t *vl = p.vt_lo + kv_head * kHeadDim * p.Spad;
+    const float c1 = p.scale * kLog2e, c0 = -p.phi * kLog2e;      // log2 of e^{s x - phi} = c1 x + c0
+    const float lo2 = p.lo * kLog2e, hi2 = p.hi * kLog2e;
+
+    // Q^T as the B operand: lane (n, g) holds d = 32 kb + 8g .. +7 of query i0 + 16 qb + n
+    f16x8 qB[4][4];
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        const int row = min(i0 + 16 * qb + n, p.Smax - 1);
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+            qB[qb][kb] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g));
+    }
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) acc[dt][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) { den[qb] = 0.f; mrun[qb] = -INFINITY; }
+
+    const int last_q = min(i0 + kQTile, S) - 1;          // last query row of the tile that exists
+    const int nsteps = last_q / kStep + 1;               // key steps 0 .. nsteps - 1 hold a key some row sees
+    auto load_k = [&](int k0, u32x4 (&kk)[2][4]) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int key = min(k0 + 8 * (n >> 2) + 4 * t + (n & 3), p.Smax - 1);
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+                kk[t][kb] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * kHeadDim + 32 * kb + 8 * g);
+        }
+    };
+    u32x4 kcur[2][4], knext[2][4];
+    if (wave < nsteps) load_k(wave * kStep, kcur);
+#pragma unroll 1
+    for (int s = wave; s < nsteps; s += 4) {
+        const int k0 = s * kStep;
+        // this step's V^T tiles (consumed after the weights are ready) and the next step's K
+        u32x4 vhh[8], vll[8];
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const size_t at = (size_t)(16 * dt + n) * p.Spad + k0 + 8 * g;
+            vhh[dt] = *reinterpret_cast<const u32x4 *>(vh + at);
+            vll[dt] = *reinterpret_cast<const u32x4 *>(vl + at);
+        }
+        load_k(min(s + 4, nsteps - 1) * kStep, knext);   // clamped: the last prefetch re-reads a live step
+        __builtin_amdgcn_sched_barrier(0);
+
+        // scores: sc[t][qb][r] = <q, k>, key k0 + 8g + 4t + r, query i0 + 16 qb + n
+        f32x4 sc[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int qb = 0; qb < 4; ++qb) {
+                f32x4 a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb)
+                    a = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[t][kb]), qB[qb][kb], a, 0, 0, 0);
+                sc[t][qb] = a;
+            }
+        // weights
+        bf16x8 pB[4], pBl[4];
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+            const int qrow = i0 + 16 * qb + n;
+            float z[8];                                  // log2 of the weight before any maximum
+            bool ok[8];
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = k0 + 8 * g + 4 * t + r;
+                    ok[4 * t + r] = (key <= qrow) & (qrow < S);
+                    z[4 * t + r] = sc[t][qb][r] * c1 + c0;
+                    bad |= ok[4 * t + r] & !((z[4 * t + r] > lo2) & (z[4 * t + r] < hi2));
+                }
+            float shift = 0.f;
+            if constexpr (ONLINE) {
+                float m = -INFINITY;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) m = fmaxf(m, ok[j] ? z[j] : -INFINITY);
+                m = fmaxf(m, __shfl_xor(m, 16));
+                m = fmaxf(m, __shfl_xor(m, 32));
+                const float mnew = fmaxf(mrun[qb], m);
+                // rescale what this wavefront has summed for the query so far
+                const float alpha = mrun[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun[qb] - mnew);
+                if (mnew > mrun[qb]) {
+#pragma unroll
+                    for (int dt = 0; dt < 8; ++dt) acc[dt][qb] *= alpha;
+                    den[qb] *= alpha;
+                    mrun[qb] = mnew;
+                }
+                shift = mnew == -INFINITY ? 0.f : mnew;
+            }
+            unsigned w[8], wl[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float e = ok[j] ? __builtin_amdgcn_exp2f(z[j] - shift) : 0.f;
+                w[j] = bf16_bits(e);
+                const float rest = e - bf16_value(w[j]);             // exact
+                wl[j] = bf16_bits(rest);
+                den[qb] += bf16_value(w[j]) + bf16_value(wl[j]);     // the weight the products will see
+            }
+            const u32x4 packed = {w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)};
+            const u32x4 packed_lo = {wl[0] | (wl[1] << 16), wl[2] | (wl[3] << 16), wl[4] | (wl[5] << 16), wl[6] | (wl[7] << 16)};
+            pB[qb] = __builtin_bit_cast(bf16x8, packed);
+            pBl[qb] = __builtin_bit_cast(bf16x8, packed_lo);
+        }
+        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise)
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+            for (int qb = 0; qb < 4; ++qb) {
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pB[qb], acc[dt][qb], 0, 0, 0);
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vll[dt]), pB[qb], acc[dt][qb], 0, 0, 0);
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pBl[qb], acc[dt][qb], 0, 0, 0);
+            }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) kcur[t][kb] = knext[t][kb];
+    }
+    // the four lane groups of a query hold disjoint keys: total per query
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        den[qb] += __shfl_xor(den[qb], 16);
+        den[qb] += __shfl_xor(den[qb], 32);
+    }
+}
+
+// Adds wavefront `from`'s partial result (in LDS slot `slot`) to this wavefront's; Eq. 2 when ONLINE.
+template <bool ONLINE>
+__device__ __forceinline__ void merge_from(PrefillLds &lds, int slot, int from, int lane, f32x4 (&acc)[8][4],
+                                           float (&den)[4], float (&mrun)[4])
+{
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        float fa = 1.f, fb = 1.f;
+        const float dn = lds.den[from][qb][lane];
+        if constexpr (ONLINE) {
+            const float mb = lds.mx[from][qb][lane];
+            const float M = fmaxf(mrun[qb], mb);
+            fa = mrun[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun[qb] - M);
+            fb = mb == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mb - M);
+            mrun[qb] = M;
+        }
+        den[qb] = den[qb] * fa + dn * fb;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[dt][qb][r] = acc[dt][qb][r] * fa + lds.buf[slot][(dt * 4 + qb) * 4 + r][lane] * fb;
+    }
+}
+
+__device__ __forceinline__ void publish(PrefillLds &lds, int slot, int wave, int lane, const f32x4 (&acc)[8][4],
+                                        const float (&den)[4], const float (&mrun)[4])
+{
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) {
+        lds.den[wave][qb][lane] = den[qb];
+        lds.mx[wave][qb][lane] = mrun[qb];
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lds.buf[slot][(dt * 4 + qb) * 4 + r][lane] = acc[dt][qb][r];
+    }
+}
+
+template <bool ONLINE>
+__device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    f32x4 acc[8][4];
+    float den[4], mrun[4];
+    bool bad = false;
+    tile_pass<ONLINE>(p, b, hq, i0, S, wave, lane, acc, den, mrun, bad);
+    const unsigned long long any = __ballot(bad);
+    if (lane == 0) lds.bad[wave] = any != 0ull;
+    // sum over the wavefronts, two at a time: 2 -> 0 and 3 -> 1, then 1 -> 0
+    if (wave >= 2) publish(lds, wave - 2, wave, lane, acc, den, mrun);
+    __syncthreads();
+    const bool flagged = (lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3]) != 0;
+    if (!ONLINE && flagged) return true;                 // uniform: the tile is redone, nothing stored
+    if (wave < 2) merge_from<ONLINE>(lds, wave, wave + 2, lane, acc, den, mrun);
+    __syncthreads();
+    if (wave == 1) publish(lds, 0, 1, lane, acc, den, mrun);
+    __syncthreads();
+    if (wave == 0) {
+        merge_from<ONLINE>(lds, 0, 1, lane, acc, den, mrun);
+        const int n = lane & 15, g = lane >> 4;
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+            const int row = i0 + 16 * qb + n;
+            if (row >= p.Smax) continue;
+            const bool live = row < S;
+            const float inv = live ? 1.f / den[qb] : 0.f;
+            uint16_t *o = p.out + (((size_t)b * p.Hq + hq) * p.Smax + row) * kHeadDim;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) {
+                uint2 h = make_uint2(0u, 0u);
+                if (live) {
+                    h.x = (unsigned)to_half_bits(acc[dt][qb][0] * inv) | ((unsigned)to_half_bits(acc[dt][qb][1] * inv) << 16);
+                    h.y = (unsigned)to_half_bits(acc[dt][qb][2] * inv) | ((unsigned)to_half_bits(acc[dt][qb][3] * inv) << 16);
+                }
+                *reinterpret_cast<uint2 *>(o + 16 * dt + 4 * g) = h;
+            }
+        }
+    }
+    return flagged;
+}
+
+__global__ __launch_bounds__(256) void prefill_kernel(const PrefillProblem p)
+{
+    __shared__ PrefillLds lds;
+    // heavy tiles (late queries see more keys) first
+    const int qt = p.tiles - 1 - (int)blockIdx.x;
+    const int hq = blockIdx.y, b = blockIdx.z;
+    const int i0 = qt * kQTile;
+    int S = p.seq_lens[b];
+    S = S < 0 ? 0 : (S > p.Smax ? p.Smax : S);
+    const size_t flag_at = ((size_t)b * p.Hq + hq) * p.tiles + qt;
+    if (i0 >= S) {                                       // no prompt token in this tile: zeros, no flag
+        uint16_t *o = p.out + (((size_t)b * p.Hq + hq) * p.Smax + i0) * kHeadDim;
+        const int rows = min(kQTile, p.Smax - i0);
+        for (int i = threadIdx.x; i < rows * (kHeadDim / 8); i += 256)
+            reinterpret_cast<u32x4 *>(o)[i] = u32x4{0u, 0u, 0u, 0u};
+        if (threadIdx.x == 0) p.tile_flags[flag_at] = 0;
+        return;
+    }
+    const bool flagged = tile_all<false>(p, lds, b, hq, i0, S);
+    if (flagged) {                                       // Section 3 "Recomputation", for this tile
+        __syncthreads();
+        tile_all<true>(p, lds, b, hq, i0, S);
+    }
+    if (threadIdx.x == 0) p.tile_flags[flag_at] = flagged ? 1 : 0;
+}
+
+}  // namespace
+
+hipError_t launch_prefill(const PrefillProblem &p, hipStream_t s)
+{
+    if (p.B == 0) return hipSuccess;
+    hipError_t e = launch(transpose_v_kernel, dim3(p.Spad / 64, p.B * p.Hkv), dim3(256), s, p);
+    if (e != hipSuccess) return e;
+    return launch(prefill_kernel, dim3(p.tiles, p.Hq, p.B), dim3(256), s, p);
+}
+
+}  // namespace fd

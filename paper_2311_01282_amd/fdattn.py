@@ -87,7 +87,14 @@ _lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _
 _lib.fd_decode_attn_append.restype = ctypes.c_int
 _lib.fd_decode_attn_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
 
-EXPORTS = ("fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+_lib.fd_prefill_workspace_bytes.restype = ctypes.c_size_t
+_lib.fd_prefill_workspace_bytes.argtypes = [_sp]
+_lib.fd_prefill_attn.restype = ctypes.c_int
+_lib.fd_prefill_attn.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+_lib.fd_prefill_get_flags.restype = ctypes.c_int
+_lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
+
+EXPORTS = ("fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
@@ -191,3 +198,19 @@ def fd_calibrate(hist, n_bins, x_min, bin_width, coverage, margin, phi_position,
 def fd_decode_attn_append(shape, q, k_new, v_new, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
     _check(_lib.fd_decode_attn_append(ctypes.byref(shape), q, k_new, v_new, k_cache, v_cache, seq_lens, phi,
                                       Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_prefill_workspace_bytes(shape):
+    return int(_lib.fd_prefill_workspace_bytes(ctypes.byref(shape)))
+
+
+def fd_prefill_attn(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_prefill_attn(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi, Bounds(*bounds), out,
+                                Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_prefill_get_flags(shape, ws_ptr, ws_bytes):
+    """Device address of tile_flags."""
+    out = _vp()
+    _check(_lib.fd_prefill_get_flags(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes), ctypes.byref(out)))
+    return out.value

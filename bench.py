@@ -43,10 +43,87 @@ def parse():
                                                         "fd_decode_attn_multikernel", "fd_decode_attn_sync"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline and overflow A/B")
+    ap.add_argument("--prefill", type=int, default=0, metavar="S",
+                    help="time the prompt phase instead (fd_prefill_attn): batch 1, 32 heads, prompt of S tokens")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 8 plain device copies of 256 MiB (a kernel of known traffic, for scaling "
                          "hardware counters collected over this command)")
     return ap.parse_args()
+
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix-core peak
+
+
+def prefill(args):
+    """Prompt phase: one fd_prefill_attn call per step on a seeded synthetic prompt."""
+    import numpy as np
+    import torch
+    from paper_2311_01282_amd import fdattn, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, H, D, S = 1, 32, 128, args.prefill
+    scale = float(np.float32(1.0 / np.sqrt(D)))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6000 + S)
+    q, k, v = (torch.randn((B, H, S, D), generator=gen, device=dev, dtype=torch.float32).half() for _ in range(3))
+    sl = torch.full((B,), S, dtype=torch.int32, device=dev)
+    out = torch.empty_like(q)
+    shape = fdattn.make_shape(B, H, H, D, S, 0, scale)
+    nws = fdattn.fd_prefill_workspace_bytes(shape)
+    ws = torch.empty(nws, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def step():
+        fdattn.fd_prefill_attn(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), synth.PHI, synth.BOUNDS,
+                               out.data_ptr(), ws.data_ptr(), nws, stream)
+    # correctness of what is timed: a seeded sample of rows against the oracle
+    from oracle import fd_prefill_oracle as pf
+    step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(S)
+    rows = np.stack([np.zeros(96, dtype=np.int32), rng.integers(0, H, 96).astype(np.int32),
+                     np.concatenate([rng.integers(0, S, 64), np.arange(S - 32, S)]).astype(np.int32)], axis=1)
+    ncpu = min(os.cpu_count() or 1, 16)
+    qn, kn, vn = q.cpu().numpy(), k.cpu().numpy(), v.cpu().numpy()
+    t0 = time.perf_counter()
+    want, _, _ = pf.prefill_rows(qn, kn, vn, sl.cpu().numpy(), scale, rows, nthreads=ncpu)
+    t_cpu = time.perf_counter() - t0
+    got = out.cpu().numpy().astype(np.float64)[rows[:, 0], rows[:, 1], rows[:, 2]]
+    max_abs = float(np.abs(got - want).max())
+    if not (max_abs <= 2e-3):
+        print("bench.py: GPU prefill result differs from the oracle (max-abs %.3e)" % max_abs, file=sys.stderr)
+        return 1
+    steps, warmup = max(5, args.steps // 32), max(2, args.warmup // 16)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    pairs = B * H * S * (S + 1) // 2                      # (query, key) pairs under the causal mask
+    flops = 4.0 * D * pairs                               # q.k and p.v, multiply + add
+    cpu_pairs = int((rows[:, 2] + 1).sum())
+    line = {
+        "metric": "prefill_attention_throughput", "value": round(flops / sec / 1e12, 1), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "prefill_b1_h32_s%d" % S, "entry": "fd_prefill_attn", "batch": B, "n_q_heads": H,
+                   "n_kv_heads": H, "head_dim": D, "prompt": S, "causal": True, "phi": synth.PHI,
+                   "bounds": list(synth.BOUNDS), "kv_dtype": "f16", "launches_per_step": 2},
+        "parity_max_abs_vs_oracle": max_abs,
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / sec / 1e12, 1),
+                     "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(flops / sec / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                     "algorithmic_flops_per_launch": flops,
+                     "note": "whole call (transpose pass + attention); useful flops 4*D per causal (query, key) pair; "
+                             "the kernel issues 2x that on the matrix cores (bf16 hi+lo operands)", "traffic": None},
+        "cpu_baseline": {"value": round(4.0 * D * cpu_pairs / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": ncpu,
+                         "kind": "oracle", "sample": "%d sampled query rows of the same prompt (%d query-key pairs), fp64"
+                                                      % (len(rows), cpu_pairs)},
+    }
+    print(json.dumps(line))
+    return 0
 
 
 def main():
@@ -63,6 +140,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.prefill:
+        return prefill(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 

@@ -33,6 +33,8 @@ namespace {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kQTile = 64;       // query rows per workgroup
 constexpr int kStep = 32;        // keys per wavefront step
@@ -96,6 +98,7 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
 }
 
 struct PrefillLds {
+    u32x4 q[4][4][64];           // Q^T B operands of the tile, [query block][kb][lane]: 16 KiB, read per MFMA
     float buf[2][128][64];       // two wavefronts' accumulators, [register][lane]
     float den[4][4][64];         // [wave][query block][lane]
     float mx[4][4][64];
@@ -104,8 +107,8 @@ struct PrefillLds {
 
 // One pass over the keys of a query tile by one wavefront.  ONLINE: running maximum.
 template <bool ONLINE>
-__device__ __forceinline__ void tile_pass(const PrefillProblem &p, int b, int hq, int i0, int S, int wave, int lane,
-                                          f32x4 (&acc)[8][4], float (&den)[4], float (&mrun)[4], bool &bad)
+__device__ __forceinline__ void tile_pass(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S, int wave,
+                                          int lane, f32x4 (&acc)[8][4], float (&den)[4], float (&mrun)[4], bool &bad)
 {
     const int n = lane & 15, g = lane >> 4;
     const int hkv = hq / p.G;
@@ -117,15 +120,16 @@ __device__ __forceinline__ void tile_pass(const PrefillProblem &p, int b, int hq
     const float c1 = p.scale * kLog2e, c0 = -p.phi * kLog2e;      // log2 of e^{s x - phi} = c1 x + c0
     const float lo2 = p.lo * kLog2e, hi2 = p.hi * kLog2e;
 
-    // Q^T as the B operand: lane (n, g) holds d = 32 kb + 8g .. +7 of query i0 + 16 qb + n
-    f16x8 qB[4][4];
-#pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
-        const int row = min(i0 + 16 * qb + n, p.Smax - 1);
+    // Q^T as the B operand: lane (n, g) needs d = 32 kb + 8g .. +7 of query i0 + 16 qb + n.  The tile's
+    // operands sit in LDS in exactly that form (64 registers per lane otherwise); wavefront w
+    // fetches query block w for all four.
+    {
+        const int row = min(i0 + 16 * wave + n, p.Smax - 1);
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
-            qB[qb][kb] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g));
+            lds.q[wave][kb][lane] = *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g);
     }
+    __syncthreads();
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
@@ -144,12 +148,67 @@ __device__ __forceinline__ void tile_pass(const PrefillProblem &p, int b, int hq
                 kk[t][kb] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * kHeadDim + 32 * kb + 8 * g);
         }
     };
-    u32x4 kcur[2][4], knext[2][4];
-    if (wave < nsteps) load_k(wave * kStep, kcur);
-#pragma unroll 1
-    for (int s = wave; s < nsteps; s += 4) {
+    // Scores of one step -> the weights as bf16 hi / lo B operands.  Works on log2 of the weight:
+    // z = log2(e) (s x - phi).  MASKED applies the causal mask and the prompt length.
+    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2][4], bf16x8 &pB, bf16x8 &pBl, int k0) {
+        constexpr bool MASKED = decltype(masked)::value;
+        const int qrow = i0 + 16 * qb + n;
+        float z[8];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][qb][r], c1, c0);
+        float zmin, zmax;
+        if constexpr (MASKED) {
+            const int kmax = qrow < S ? qrow : -1;                   // last key this query sees
+            float zl[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: keys k0 + 8g + j
+                zl[j] = ok ? z[j] : INFINITY;
+                z[j] = ok ? z[j] : -INFINITY;                        // weight 0
+            }
+            zmin = fminf(fminf(fminf(zl[0], zl[1]), fminf(zl[2], zl[3])), fminf(fminf(zl[4], zl[5]), fminf(zl[6], zl[7])));
+        } else {
+            zmin = fminf(fminf(fminf(z[0], z[1]), fminf(z[2], z[3])), fminf(fminf(z[4], z[5]), fminf(z[6], z[7])));
+        }
+        zmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+        // guard on the extremes (strict; a masked-out lane group has zmin = +inf, zmax = -inf)
+        bad |= (zmax >= hi2) | (zmin <= lo2);
+        float shift = 0.f;
+        if constexpr (ONLINE) {
+            float m = zmax;
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            const float mnew = fmaxf(mrun[qb], m);
+            if (mnew > mrun[qb]) {                                   // rescale what was summed so far
+                const float alpha = mrun[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun[qb] - mnew);
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) acc[dt][qb] *= alpha;
+                den[qb] *= alpha;
+                mrun[qb] = mnew;
+            }
+            shift = mnew == -INFINITY ? 0.f : mnew;
+        }
+        unsigned hi[4], lo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f32x2 e = {__builtin_amdgcn_exp2f(z[2 * j] - shift), __builtin_amdgcn_exp2f(z[2 * j + 1] - shift)};
+            den[qb] += e[0] + e[1];
+            hi[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
+            const f32x2 top = {__builtin_bit_cast(float, hi[j] << 16), __builtin_bit_cast(float, hi[j] & 0xffff0000u)};
+            lo[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e - top, bf16x2));        // e - top is exact
+        }
+        pB = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
+        pBl = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
+    };
+    u32x4 kcur[2][4];
+    // One 32-key step, straight-line: the matrix cores and the vector ALU work on different
+    // query blocks at the same time (scores of block qb + 1 and products of block qb - 1 run
+    // under the exponentials of block qb); the scheduling groups at the end spell that out.
+    auto step = [&](auto masked, int s) {
         const int k0 = s * kStep;
-        // this step's V^T tiles (consumed after the weights are ready) and the next step's K
+        // this step's V^T tiles (consumed after the weights are ready)
         u32x4 vhh[8], vll[8];
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
@@ -157,82 +216,59 @@ __device__ __forceinline__ void tile_pass(const PrefillProblem &p, int b, int hq
             vhh[dt] = *reinterpret_cast<const u32x4 *>(vh + at);
             vll[dt] = *reinterpret_cast<const u32x4 *>(vl + at);
         }
-        load_k(min(s + 4, nsteps - 1) * kStep, knext);   // clamped: the last prefetch re-reads a live step
-        __builtin_amdgcn_sched_barrier(0);
-
         // scores: sc[t][qb][r] = <q, k>, key k0 + 8g + 4t + r, query i0 + 16 qb + n
         f32x4 sc[2][4];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int qb = 0; qb < 4; ++qb) {
+            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int qb = 0; qb < 4; ++qb) {
-                f32x4 a = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int kb = 0; kb < 4; ++kb)
-                    a = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[t][kb]), qB[qb][kb], a, 0, 0, 0);
-                sc[t][qb] = a;
+            for (int kb = 0; kb < 4; ++kb) {
+                const f16x8 qv = __builtin_bit_cast(f16x8, lds.q[qb][kb][lane]);
+                a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[0][kb]), qv, a0, 0, 0, 0);
+                a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[1][kb]), qv, a1, 0, 0, 0);
             }
-        // weights
-        bf16x8 pB[4], pBl[4];
+            sc[0][qb] = a0;
+            sc[1][qb] = a1;
+        }
+        // the next step's K goes into the registers the scores just freed (the last prefetch,
+        // clamped, re-reads a live step)
+        load_k(min(s + 4, nsteps - 1) * kStep, kcur);
+        // per query block: weights, then O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl:
+        // Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise), product-major so that dependent
+        // MFMAs are 8 apart
 #pragma unroll
         for (int qb = 0; qb < 4; ++qb) {
-            const int qrow = i0 + 16 * qb + n;
-            float z[8];                                  // log2 of the weight before any maximum
-            bool ok[8];
+            bf16x8 pB, pBl;
+            weights(masked, qb, sc, pB, pBl, k0);
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+            for (int dt = 0; dt < 8; ++dt)
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pB, acc[dt][qb], 0, 0, 0);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = k0 + 8 * g + 4 * t + r;
-                    ok[4 * t + r] = (key <= qrow) & (qrow < S);
-                    z[4 * t + r] = sc[t][qb][r] * c1 + c0;
-                    bad |= ok[4 * t + r] & !((z[4 * t + r] > lo2) & (z[4 * t + r] < hi2));
-                }
-            float shift = 0.f;
-            if constexpr (ONLINE) {
-                float m = -INFINITY;
+            for (int dt = 0; dt < 8; ++dt)
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vll[dt]), pB, acc[dt][qb], 0, 0, 0);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) m = fmaxf(m, ok[j] ? z[j] : -INFINITY);
-                m = fmaxf(m, __shfl_xor(m, 16));
-                m = fmaxf(m, __shfl_xor(m, 32));
-                const float mnew = fmaxf(mrun[qb], m);
-                // rescale what this wavefront has summed for the query so far
-                const float alpha = mrun[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun[qb] - mnew);
-                if (mnew > mrun[qb]) {
-#pragma unroll
-                    for (int dt = 0; dt < 8; ++dt) acc[dt][qb] *= alpha;
-                    den[qb] *= alpha;
-                    mrun[qb] = mnew;
-                }
-                shift = mnew == -INFINITY ? 0.f : mnew;
-            }
-            unsigned w[8], wl[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float e = ok[j] ? __builtin_amdgcn_exp2f(z[j] - shift) : 0.f;
-                w[j] = bf16_bits(e);
-                const float rest = e - bf16_value(w[j]);             // exact
-                wl[j] = bf16_bits(rest);
-                den[qb] += bf16_value(w[j]) + bf16_value(wl[j]);     // the weight the products will see
-            }
-            const u32x4 packed = {w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16)};
-            const u32x4 packed_lo = {wl[0] | (wl[1] << 16), wl[2] | (wl[3] << 16), wl[4] | (wl[5] << 16), wl[6] | (wl[7] << 16)};
-            pB[qb] = __builtin_bit_cast(bf16x8, packed);
-            pBl[qb] = __builtin_bit_cast(bf16x8, packed_lo);
+            for (int dt = 0; dt < 8; ++dt)
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pBl, acc[dt][qb], 0, 0, 0);
         }
-        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise)
+        // issue order: 8 score MFMAs, then one MFMA per four vector instructions while there are
+        // vector instructions left (about 70 per query block), then the remaining MFMAs
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
+        for (int i = 0; i < 8; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
-            for (int qb = 0; qb < 4; ++qb) {
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pB[qb], acc[dt][qb], 0, 0, 0);
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vll[dt]), pB[qb], acc[dt][qb], 0, 0, 0);
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pBl[qb], acc[dt][qb], 0, 0, 0);
-            }
+        for (int i = 0; i < 96; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb) kcur[t][kb] = knext[t][kb];
+        for (int i = 0; i < 24; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    };
+    if (wave < nsteps) load_k(wave * kStep, kcur);
+#pragma unroll 1
+    for (int s = wave; s < nsteps; s += 4) {
+        // steps that lie entirely below the diagonal of the tile, in a tile whose 64 queries all
+        // exist, need no mask
+        if (s * kStep + kStep - 1 <= i0 && i0 + kQTile <= S) step(std::false_type{}, s);
+        else step(std::true_type{}, s);
     }
     // the four lane groups of a query hold disjoint keys: total per query
 #pragma unroll
@@ -288,7 +324,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     f32x4 acc[8][4];
     float den[4], mrun[4];
     bool bad = false;
-    tile_pass<ONLINE>(p, b, hq, i0, S, wave, lane, acc, den, mrun, bad);
+    tile_pass<ONLINE>(p, lds, b, hq, i0, S, wave, lane, acc, den, mrun, bad);
     const unsigned long long any = __ballot(bad);
     if (lane == 0) lds.bad[wave] = any != 0ull;
     // sum over the wavefronts, two at a time: 2 -> 0 and 3 -> 1, then 1 -> 0
@@ -327,9 +363,19 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
 __global__ __launch_bounds__(256) void prefill_kernel(const PrefillProblem p)
 {
     __shared__ PrefillLds lds;
-    // heavy tiles (late queries see more keys) first
-    const int qt = p.tiles - 1 - (int)blockIdx.x;
-    const int hq = blockIdx.y, b = blockIdx.z;
+    // Workgroups are dealt to the 8 XCDs round-robin by index; each XCD has its own L2.  All
+    // tiles of the query heads that share one KV head go to the same XCD, one KV head after the
+    // other, so that the K and V^T an XCD streams at any time belong to one head and its tiles
+    // walk the keys together (the reads then hit in that L2 instead of going to memory eight
+    // times).  Within a head, heavy tiles (late queries see more keys) first.
+    const int j = blockIdx.x >> 3;
+    const int per_group = p.G * p.tiles;
+    const int gi = (blockIdx.x & 7) + 8 * (j / per_group);       // (sequence, KV head)
+    if (gi >= p.B * p.Hkv) return;
+    const int r = j % per_group;
+    const int qt = p.tiles - 1 - r % p.tiles;
+    const int b = gi / p.Hkv;
+    const int hq = (gi - b * p.Hkv) * p.G + r / p.tiles;
     const int i0 = qt * kQTile;
     int S = p.seq_lens[b];
     S = S < 0 ? 0 : (S > p.Smax ? p.Smax : S);
@@ -357,7 +403,8 @@ hipError_t launch_prefill(const PrefillProblem &p, hipStream_t s)
     if (p.B == 0) return hipSuccess;
     hipError_t e = launch(transpose_v_kernel, dim3(p.Spad / 64, p.B * p.Hkv), dim3(256), s, p);
     if (e != hipSuccess) return e;
-    return launch(prefill_kernel, dim3(p.tiles, p.Hq, p.B), dim3(256), s, p);
+    const long long groups8 = ((long long)p.B * p.Hkv + 7) / 8 * 8;
+    return launch(prefill_kernel, dim3((unsigned)(groups8 * p.G * p.tiles)), dim3(256), s, p);
 }
 
 }  // namespace fd

@@ -62,7 +62,9 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     if (tid == 0) lds.last = arrive_and_elect(p, row, c, nb);
     __syncthreads();
     if (!lds.last) return;
-    row_epilogue<NW, true>(p, row, nb, [nb] { return nb; }, &lds.acc[0][0]);
+    // up to 8 chunks: 32 threads walk them in registers (one round trip, no LDS, no barrier)
+    if (nb <= 8) group_epilogue(p, row, 1, nb);
+    else row_epilogue<NW, true>(p, row, nb, [nb] { return nb; }, &lds.acc[0][0]);
 }
 
 template <int C>

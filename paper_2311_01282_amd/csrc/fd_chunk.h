@@ -562,16 +562,28 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_lo
 // the plain sum of Eq. 4).  No thread needs another's data: one memory round trip
 // per 4 chunks, two batches in flight, no LDS and no barrier.  Loads pass the caches
 // (the partial results come from other workgroups of the same launch).
-__device__ __forceinline__ void group_epilogue(const Problem &p, int row0, int G, int nb)
+// COHERENT = false and a per-row chunk count serve a launch of its own over arbitrary rows.
+template <bool COHERENT = true, typename NbFn>
+__device__ __forceinline__ void rows_epilogue(const Problem &p, int row0, int G, NbFn nb_of)
 {
     const int tid = threadIdx.x, t4 = tid & 31;
     auto ld16 = [](const void *ptr) {
-        const unsigned long long *w = static_cast<const unsigned long long *>(ptr);
-        const unsigned long long a = load_coherent(&w[0]), b = load_coherent(&w[1]);
-        return u32x4{(unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32)};
+        if constexpr (COHERENT) {
+            const unsigned long long *w = static_cast<const unsigned long long *>(ptr);
+            const unsigned long long a = load_coherent(&w[0]), b = load_coherent(&w[1]);
+            return u32x4{(unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32)};
+        } else {
+            return *static_cast<const u32x4 *>(ptr);
+        }
     };
     for (int h = tid >> 5; h < G; h += 8) {
         const int row = row0 + h;
+        const int nb = nb_of(row);
+        if (nb <= 0) {                          // (only a launch of its own gets here: empty sequence)
+            *reinterpret_cast<uint2 *>(p.out + (size_t)row * kHeadDim + 4 * t4) = make_uint2(0u, 0u);
+            if (t4 == 0) p.ws.row_flags[row] = 0;
+            continue;
+        }
         const size_t r0 = (size_t)row * p.nc;
         const float *num = p.ws.num + r0 * kHeadDim + 4 * t4;
         const SlotMeta *meta = p.ws.meta + r0;
@@ -629,6 +641,10 @@ __device__ __forceinline__ void group_epilogue(const Problem &p, int row0, int G
         *reinterpret_cast<uint2 *>(p.out + (size_t)row * kHeadDim + 4 * t4) = o;
         if (t4 == 0) p.ws.row_flags[row] = f ? 1 : 0;
     }
+}
+__device__ __forceinline__ void group_epilogue(const Problem &p, int row0, int G, int nb)
+{
+    rows_epilogue<true>(p, row0, G, [nb](int) { return nb; });
 }
 
 // Elects the workgroup that completes a row: a radix-8 tree of arrival counters

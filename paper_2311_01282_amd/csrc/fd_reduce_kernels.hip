@@ -25,6 +25,14 @@ __global__ __launch_bounds__(256) void row_epilogue_kernel(const Problem p)
     row_epilogue<4, false>(p, row, p.nc, [&] { return (valid_len(p, row / p.Hq) + p.C - 1) / p.C; }, scratch);
 }
 
+// The same for rows of at most 8 chunks: 8 rows per workgroup, 32 threads per row walking
+// the row's chunks in registers (no LDS, no barrier, an eighth of the workgroups).
+__global__ __launch_bounds__(256) void rows8_epilogue_kernel(const Problem p)
+{
+    const int row0 = blockIdx.x * 8;
+    rows_epilogue<false>(p, row0, min(8, p.rows - row0), [&](int row) { return (valid_len(p, row / p.Hq) + p.C - 1) / p.C; });
+}
+
 // Chunk flags -> row flags, ascending list of flagged rows, their count.
 // A single workgroup: the compaction is a block-wide prefix sum, no atomics.
 __global__ __launch_bounds__(1024) void flag_reduce_kernel(const Problem p)
@@ -117,6 +125,7 @@ hipError_t launch_clear_tickets(const Problem &p, hipStream_t s)
 hipError_t launch_row_epilogue(const Problem &p, hipStream_t s)
 {
     if (p.rows == 0) return hipSuccess;
+    if (p.nc <= 8) return launch(rows8_epilogue_kernel, dim3((p.rows + 7) / 8), dim3(256), s, p);
     return launch(row_epilogue_kernel, dim3(p.rows), dim3(256), s, p);
 }
 

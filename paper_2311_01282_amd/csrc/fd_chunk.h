@@ -373,7 +373,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
                 den += e;
                 // the appended V row for its key, and for every key when no resident row was
                 // there to clamp to (weight zero then, but the cache may hold anything)
-                axpy8(acc, e, (kidx == jnew) | (nres <= 0) ? vn : vv[u]);
+                axpy8(acc, e, ((kidx == jnew) | (nres <= 0)) ? vn : vv[u]);
             }
         }
         if (owner && hq == hkv * p.G && wave == 0 && sub == 0 && p.k_store) {

@@ -123,3 +123,35 @@ def test_hand_over_is_stable_over_many_calls(oracle, H):
     got = outs.cpu().numpy().astype(np.float64)
     for i in range(n):
         assert np.array_equal(got[i], ref[i % 2]), "call %d differs from the first call on the same cache" % i
+
+
+def test_calls_can_be_captured_in_a_graph_and_replayed(oracle, H):
+    """The calls allocate nothing, synchronise nothing and leave their arrival counters at zero, so a
+    stream capture of them replays: per-row and grouped entry points, single- and two-launch grids,
+    each replayed five times with eager work in between and compared with the eager result."""
+    import torch
+    for (B, Hq, Hkv, Smax, chunk, entry) in ((1, 32, 32, 2048, 256, "fd_decode_attn"),        # 256 workgroups: one launch
+                                             (8, 32, 32, 2048, 256, "fd_decode_attn"),        # 2048: two launches
+                                             (4, 64, 8, 1024, 256, "fd_decode_attn_gqa")):
+        case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=8800 + B)
+        dc = H.DeviceCase(case, chunk=chunk)
+        want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=8)
+        eager = dc.run(entry)
+        H.assert_close(eager, want, "eager")
+        side = torch.cuda.Stream(device=dc.dev)
+        graph = torch.cuda.CUDAGraph()
+        out_g = torch.full_like(dc.out, float("nan"))
+        side.wait_stream(torch.cuda.current_stream(dc.dev))
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                getattr(fdattn, entry)(*dc._args(), synth.PHI, synth.BOUNDS, out_g.data_ptr(), *dc._ws(), side.cuda_stream)
+        torch.cuda.synchronize(dc.dev)
+        for i in range(5):
+            out_g.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize(dc.dev)
+            got = out_g.cpu().numpy().astype(np.float64)
+            assert np.array_equal(got, eager), "replay %d differs from the eager call" % i
+            again = dc.run(entry)                        # eager work on the same workspace between replays
+            assert np.array_equal(again, eager)
+        del graph

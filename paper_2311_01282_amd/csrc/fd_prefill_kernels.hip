@@ -36,7 +36,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kQTile = 64;       // query rows per workgroup
+constexpr int kQTile = 128;      // query rows per workgroup
 constexpr int kStep = 32;        // keys per wavefront step
 
 // fp32 -> bf16 bit pattern, round to nearest even (finite inputs; NaN stays NaN).
@@ -97,19 +97,33 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
     }
 }
 
+// ---- the attention kernel ----
+// A workgroup owns 128 queries of one head: wavefront w the 32 queries i0 + 32w .. +31 (two
+// blocks of 16).  The K and V^T tiles of a 32-key step are fetched once per workgroup into LDS
+// (double-buffered, one barrier per step) and read from there by all four wavefronts as MFMA A
+// operands; Q^T stays in registers as the B operand.  Every output row belongs to one wavefront:
+// nothing is reduced across wavefronts, and with the unified phi nothing is ever rescaled.
+constexpr int kKStride = 256;    // bytes per K row in LDS (16 chunks of 16 bytes, XOR-swizzled)
+constexpr int kVStride = 80;     // bytes per V^T row (32 keys = 64 bytes, padded: rows 20 dwords apart)
 struct PrefillLds {
-    u32x4 q[4][4][64];           // Q^T B operands of the tile, [query block][kb][lane]: 16 KiB, read per MFMA
-    float buf[2][128][64];       // two wavefronts' accumulators, [register][lane]
-    float den[4][4][64];         // [wave][query block][lane]
-    float mx[4][4][64];
+    alignas(16) unsigned char k[2][kStep * kKStride];          // 2 x 8 KiB
+    alignas(16) unsigned char vh[2][kHeadDim * kVStride];      // 2 x 10 KiB
+    alignas(16) unsigned char vl[2][kHeadDim * kVStride];      // 2 x 10 KiB
     int bad[4];
 };
 
-// One pass over the keys of a query tile by one wavefront.  ONLINE: running maximum.
-template <bool ONLINE>
-__device__ __forceinline__ void tile_pass(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S, int wave,
-                                          int lane, f32x4 (&acc)[8][4], float (&den)[4], float (&mrun)[4], bool &bad)
+// K row r, 16-byte chunk c -> byte offset.  The 8 lanes that read together take rows
+// {0,1,2,3,8,9,10,11} (+4, +16, ...) of one chunk: XOR with (r & 3) | ((r >> 3) & 1) << 2 sends
+// them to 8 different 16-byte bank groups; a row's 16 chunks stay a permutation of themselves.
+__device__ __forceinline__ int k_slot(int r, int c)
 {
+    return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 1) << 2))) << 4);
+}
+
+template <bool ONLINE>
+__device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;
     const int hkv = hq / p.G;
     const size_t kv_head = (size_t)b * p.Hkv + hkv;
@@ -119,52 +133,72 @@ __device__ __forceinline__ void tile_pass(const PrefillProblem &p, PrefillLds &l
     const uint16_t *vl = p.vt_lo + kv_head * kHeadDim * p.Spad;
     const float c1 = p.scale * kLog2e, c0 = -p.phi * kLog2e;      // log2 of e^{s x - phi} = c1 x + c0
     const float lo2 = p.lo * kLog2e, hi2 = p.hi * kLog2e;
+    const int w0 = i0 + 32 * wave;                       // first query of this wavefront
 
-    // Q^T as the B operand: lane (n, g) needs d = 32 kb + 8g .. +7 of query i0 + 16 qb + n.  The tile's
-    // operands sit in LDS in exactly that form (64 registers per lane otherwise); wavefront w
-    // fetches query block w for all four.
-    {
-        const int row = min(i0 + 16 * wave + n, p.Smax - 1);
+    // Q^T as the B operand: lane (n, g) holds d = 32 kb + 8g .. +7 of query w0 + 16 qb + n
+    f16x8 qB[2][4];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = min(w0 + 16 * qb + n, p.Smax - 1);
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
-            lds.q[wave][kb][lane] = *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g);
+            qB[qb][kb] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g));
     }
-    __syncthreads();
+    f32x4 acc[8][2];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) acc[dt][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int qb = 0; qb < 4; ++qb) { den[qb] = 0.f; mrun[qb] = -INFINITY; }
+        for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float den[2] = {0.f, 0.f}, mrun[2] = {-INFINITY, -INFINITY};
+    bool bad = false;
 
-    const int last_q = min(i0 + kQTile, S) - 1;          // last query row of the tile that exists
-    const int nsteps = last_q / kStep + 1;               // key steps 0 .. nsteps - 1 hold a key some row sees
-    auto load_k = [&](int k0, u32x4 (&kk)[2][4]) {
+    // key steps: the workgroup walks 0 .. nsteps - 1 (keys some query of the tile sees); this
+    // wavefront computes while a key of the step is visible to one of its queries
+    const int last_q = min(i0 + kQTile, S) - 1;
+    const int nsteps = last_q / kStep + 1;
+    const int my_last_q = min(w0 + 32, S) - 1;           // < w0 when the wavefront has no query
+    const int my_steps = my_last_q >= w0 ? my_last_q / kStep + 1 : 0;
+
+    // cooperative tile fetch: thread t moves 2 chunks of K and 2 each of V^T hi / lo per step
+    u32x4 pk[2], ph[2], pl[2];
+    auto fetch = [&](int s) {
+        const int k0 = s * kStep;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int key = min(k0 + 8 * (n >> 2) + 4 * t + (n & 3), p.Smax - 1);
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
-                kk[t][kb] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * kHeadDim + 32 * kb + 8 * g);
+        for (int i = 0; i < 2; ++i) {
+            const int id = tid + 256 * i;                // 512 chunks: K row r = id / 16, chunk c = id % 16
+            const int r = id >> 4, c = id & 15;
+            pk[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c);
+            const int d = id >> 2, gg = id & 3;          // V^T row d = id / 4, chunk gg = id % 4 (8 keys)
+            const size_t at = (size_t)d * p.Spad + k0 + 8 * gg;
+            ph[i] = *reinterpret_cast<const u32x4 *>(vh + at);
+            pl[i] = *reinterpret_cast<const u32x4 *>(vl + at);
         }
     };
-    // Scores of one step -> the weights as bf16 hi / lo B operands.  Works on log2 of the weight:
-    // z = log2(e) (s x - phi).  MASKED applies the causal mask and the prompt length.
-    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2][4], bf16x8 &pB, bf16x8 &pBl, int k0) {
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int id = tid + 256 * i;
+            *reinterpret_cast<u32x4 *>(&lds.k[buf][k_slot(id >> 4, id & 15)]) = pk[i];
+            *reinterpret_cast<u32x4 *>(&lds.vh[buf][(id >> 2) * kVStride + 16 * (id & 3)]) = ph[i];
+            *reinterpret_cast<u32x4 *>(&lds.vl[buf][(id >> 2) * kVStride + 16 * (id & 3)]) = pl[i];
+        }
+    };
+    // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
+    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2], bf16x8 &pB, bf16x8 &pBl, int k0) {
         constexpr bool MASKED = decltype(masked)::value;
-        const int qrow = i0 + 16 * qb + n;
+        const int qrow = w0 + 16 * qb + n;
         float z[8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][qb][r], c1, c0);
+            for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][r], c1, c0);
         float zmin, zmax;
         if constexpr (MASKED) {
             const int kmax = qrow < S ? qrow : -1;                   // last key this query sees
             float zl[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
-                const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: keys k0 + 8g + j
+                const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: key k0 + 8g + j
                 zl[j] = ok ? z[j] : INFINITY;
                 z[j] = ok ? z[j] : -INFINITY;                        // weight 0
             }
@@ -202,165 +236,100 @@ __device__ __forceinline__ void tile_pass(const PrefillProblem &p, PrefillLds &l
         pB = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
         pBl = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
     };
-    u32x4 kcur[2][4];
-    // One 32-key step, straight-line: the matrix cores and the vector ALU work on different
-    // query blocks at the same time (scores of block qb + 1 and products of block qb - 1 run
-    // under the exponentials of block qb); the scheduling groups at the end spell that out.
-    auto step = [&](auto masked, int s) {
+    // one step of this wavefront on the tiles in LDS buffer `buf`
+    auto compute = [&](auto masked, int s, int buf) {
         const int k0 = s * kStep;
-        // this step's V^T tiles (consumed after the weights are ready)
-        u32x4 vhh[8], vll[8];
+        // scores: row m = n of key block t is key k0 + 8 (n >> 2) + 4t + (n & 3), so that the two
+        // score tiles leave lane (n, g) holding keys k0 + 8g .. 8g + 7 of query n
+        f32x4 sc[2][2];
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            const size_t at = (size_t)(16 * dt + n) * p.Spad + k0 + 8 * g;
-            vhh[dt] = *reinterpret_cast<const u32x4 *>(vh + at);
-            vll[dt] = *reinterpret_cast<const u32x4 *>(vl + at);
-        }
-        // scores: sc[t][qb][r] = <q, k>, key k0 + 8g + 4t + r, query i0 + 16 qb + n
-        f32x4 sc[2][4];
+        for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
-            f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = {0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 2; ++t) sc[qb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int r = 8 * (n >> 2) + 4 * t + (n & 3);
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb) {
-                const f16x8 qv = __builtin_bit_cast(f16x8, lds.q[qb][kb][lane]);
-                a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[0][kb]), qv, a0, 0, 0, 0);
-                a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, kcur[1][kb]), qv, a1, 0, 0, 0);
+                const f16x8 ka = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(&lds.k[buf][k_slot(r, 4 * kb + g)]));
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb)
+                    sc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qB[qb][kb], sc[qb][t], 0, 0, 0);
             }
-            sc[0][qb] = a0;
-            sc[1][qb] = a1;
         }
-        // the next step's K goes into the registers the scores just freed (the last prefetch,
-        // clamped, re-reads a live step)
-        load_k(min(s + 4, nsteps - 1) * kStep, kcur);
-        // per query block: weights, then O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl:
-        // Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise), product-major so that dependent
-        // MFMAs are 8 apart
+        bf16x8 pB[2], pBl[2];
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
-            bf16x8 pB, pBl;
-            weights(masked, qb, sc, pB, pBl, k0);
+        for (int qb = 0; qb < 2; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
+        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise)
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pB, acc[dt][qb], 0, 0, 0);
+        for (int dt = 0; dt < 8; ++dt) {
+            const int off = (16 * dt + n) * kVStride + 16 * g;
+            const bf16x8 a_hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]));
+            const bf16x8 a_lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]));
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vll[dt]), pB, acc[dt][qb], 0, 0, 0);
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vhh[dt]), pBl, acc[dt][qb], 0, 0, 0);
+            for (int qb = 0; qb < 2; ++qb) {
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, pB[qb], acc[dt][qb], 0, 0, 0);
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, pB[qb], acc[dt][qb], 0, 0, 0);
+                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, pBl[qb], acc[dt][qb], 0, 0, 0);
+            }
         }
-        // issue order: 8 score MFMAs, then one MFMA per four vector instructions while there are
-        // vector instructions left (about 70 per query block), then the remaining MFMAs
-#pragma unroll
-        for (int i = 0; i < 8; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-#pragma unroll
-        for (int i = 0; i < 96; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 24; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     };
-    if (wave < nsteps) load_k(wave * kStep, kcur);
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
 #pragma unroll 1
-    for (int s = wave; s < nsteps; s += 4) {
-        // steps that lie entirely below the diagonal of the tile, in a tile whose 64 queries all
-        // exist, need no mask
-        if (s * kStep + kStep - 1 <= i0 && i0 + kQTile <= S) step(std::false_type{}, s);
-        else step(std::true_type{}, s);
+    for (int s = 0; s < nsteps; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < nsteps) fetch(s + 1);                // uniform over the workgroup
+        if (s < my_steps) {                              // uniform over the wavefront
+            // steps entirely below this wavefront's first query, all 32 of whose queries exist, need no mask
+            if (s * kStep + kStep - 1 <= w0 && w0 + 32 <= S) compute(std::false_type{}, s, buf);
+            else compute(std::true_type{}, s, buf);
+        }
+        if (s + 1 < nsteps) stash(buf ^ 1);              // last read in step s - 1, which every wavefront has left
+        __syncthreads();
     }
     // the four lane groups of a query hold disjoint keys: total per query
 #pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
+    for (int qb = 0; qb < 2; ++qb) {
         den[qb] += __shfl_xor(den[qb], 16);
         den[qb] += __shfl_xor(den[qb], 32);
     }
-}
-
-// Adds wavefront `from`'s partial result (in LDS slot `slot`) to this wavefront's; Eq. 2 when ONLINE.
-template <bool ONLINE>
-__device__ __forceinline__ void merge_from(PrefillLds &lds, int slot, int from, int lane, f32x4 (&acc)[8][4],
-                                           float (&den)[4], float (&mrun)[4])
-{
-#pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
-        float fa = 1.f, fb = 1.f;
-        const float dn = lds.den[from][qb][lane];
-        if constexpr (ONLINE) {
-            const float mb = lds.mx[from][qb][lane];
-            const float M = fmaxf(mrun[qb], mb);
-            fa = mrun[qb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mrun[qb] - M);
-            fb = mb == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mb - M);
-            mrun[qb] = M;
-        }
-        den[qb] = den[qb] * fa + dn * fb;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                acc[dt][qb][r] = acc[dt][qb][r] * fa + lds.buf[slot][(dt * 4 + qb) * 4 + r][lane] * fb;
-    }
-}
-
-__device__ __forceinline__ void publish(PrefillLds &lds, int slot, int wave, int lane, const f32x4 (&acc)[8][4],
-                                        const float (&den)[4], const float (&mrun)[4])
-{
-#pragma unroll
-    for (int qb = 0; qb < 4; ++qb) {
-        lds.den[wave][qb][lane] = den[qb];
-        lds.mx[wave][qb][lane] = mrun[qb];
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) lds.buf[slot][(dt * 4 + qb) * 4 + r][lane] = acc[dt][qb][r];
-    }
-}
-
-template <bool ONLINE>
-__device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    f32x4 acc[8][4];
-    float den[4], mrun[4];
-    bool bad = false;
-    tile_pass<ONLINE>(p, lds, b, hq, i0, S, wave, lane, acc, den, mrun, bad);
     const unsigned long long any = __ballot(bad);
     if (lane == 0) lds.bad[wave] = any != 0ull;
-    // sum over the wavefronts, two at a time: 2 -> 0 and 3 -> 1, then 1 -> 0
-    if (wave >= 2) publish(lds, wave - 2, wave, lane, acc, den, mrun);
     __syncthreads();
     const bool flagged = (lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3]) != 0;
-    if (!ONLINE && flagged) return true;                 // uniform: the tile is redone, nothing stored
-    if (wave < 2) merge_from<ONLINE>(lds, wave, wave + 2, lane, acc, den, mrun);
-    __syncthreads();
-    if (wave == 1) publish(lds, 0, 1, lane, acc, den, mrun);
-    __syncthreads();
-    if (wave == 0) {
-        merge_from<ONLINE>(lds, 0, 1, lane, acc, den, mrun);
-        const int n = lane & 15, g = lane >> 4;
+    if (!ONLINE) {
+        // one flag byte per 64 queries: wavefronts 0, 1 and 2, 3
+        if (tid == 0 || tid == 128) {
+            const int half = tid >> 7;
+            const int t64 = i0 / 64 + half;
+            if (t64 < p.tiles) p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + t64] = (lds.bad[2 * half] | lds.bad[2 * half + 1]) != 0;
+        }
+        if (flagged) return true;                        // uniform: the tile is redone, nothing stored
+    }
 #pragma unroll
-        for (int qb = 0; qb < 4; ++qb) {
-            const int row = i0 + 16 * qb + n;
-            if (row >= p.Smax) continue;
-            const bool live = row < S;
-            const float inv = live ? 1.f / den[qb] : 0.f;
-            uint16_t *o = p.out + (((size_t)b * p.Hq + hq) * p.Smax + row) * kHeadDim;
+    for (int qb = 0; qb < 2; ++qb) {
+        const int row = w0 + 16 * qb + n;
+        if (row >= p.Smax) continue;
+        const bool live = row < S;
+        const float inv = live ? 1.f / den[qb] : 0.f;
+        uint16_t *o = p.out + (((size_t)b * p.Hq + hq) * p.Smax + row) * kHeadDim;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
-                uint2 h = make_uint2(0u, 0u);
-                if (live) {
-                    h.x = (unsigned)to_half_bits(acc[dt][qb][0] * inv) | ((unsigned)to_half_bits(acc[dt][qb][1] * inv) << 16);
-                    h.y = (unsigned)to_half_bits(acc[dt][qb][2] * inv) | ((unsigned)to_half_bits(acc[dt][qb][3] * inv) << 16);
-                }
-                *reinterpret_cast<uint2 *>(o + 16 * dt + 4 * g) = h;
+        for (int dt = 0; dt < 8; ++dt) {
+            uint2 h = make_uint2(0u, 0u);
+            if (live) {
+                h.x = (unsigned)to_half_bits(acc[dt][qb][0] * inv) | ((unsigned)to_half_bits(acc[dt][qb][1] * inv) << 16);
+                h.y = (unsigned)to_half_bits(acc[dt][qb][2] * inv) | ((unsigned)to_half_bits(acc[dt][qb][3] * inv) << 16);
             }
+            *reinterpret_cast<uint2 *>(o + 16 * dt + 4 * g) = h;
         }
     }
     return flagged;
 }
 
-__global__ __launch_bounds__(256) void prefill_kernel(const PrefillProblem p)
+__global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillProblem p)
 {
     __shared__ PrefillLds lds;
     // Workgroups are dealt to the 8 XCDs round-robin by index; each XCD has its own L2.  All
@@ -368,24 +337,25 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillProblem p)
     // other, so that the K and V^T an XCD streams at any time belong to one head and its tiles
     // walk the keys together (the reads then hit in that L2 instead of going to memory eight
     // times).  Within a head, heavy tiles (late queries see more keys) first.
+    const int qtiles = (p.Smax + kQTile - 1) / kQTile;
     const int j = blockIdx.x >> 3;
-    const int per_group = p.G * p.tiles;
+    const int per_group = p.G * qtiles;
     const int gi = (blockIdx.x & 7) + 8 * (j / per_group);       // (sequence, KV head)
     if (gi >= p.B * p.Hkv) return;
     const int r = j % per_group;
-    const int qt = p.tiles - 1 - r % p.tiles;
+    const int qt = qtiles - 1 - r % qtiles;
     const int b = gi / p.Hkv;
-    const int hq = (gi - b * p.Hkv) * p.G + r / p.tiles;
+    const int hq = (gi - b * p.Hkv) * p.G + r / qtiles;
     const int i0 = qt * kQTile;
     int S = p.seq_lens[b];
     S = S < 0 ? 0 : (S > p.Smax ? p.Smax : S);
-    const size_t flag_at = ((size_t)b * p.Hq + hq) * p.tiles + qt;
     if (i0 >= S) {                                       // no prompt token in this tile: zeros, no flag
         uint16_t *o = p.out + (((size_t)b * p.Hq + hq) * p.Smax + i0) * kHeadDim;
         const int rows = min(kQTile, p.Smax - i0);
         for (int i = threadIdx.x; i < rows * (kHeadDim / 8); i += 256)
             reinterpret_cast<u32x4 *>(o)[i] = u32x4{0u, 0u, 0u, 0u};
-        if (threadIdx.x == 0) p.tile_flags[flag_at] = 0;
+        if (threadIdx.x < 2 && i0 / 64 + (int)threadIdx.x < p.tiles)
+            p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + i0 / 64 + threadIdx.x] = 0;
         return;
     }
     const bool flagged = tile_all<false>(p, lds, b, hq, i0, S);
@@ -393,7 +363,6 @@ __global__ __launch_bounds__(256) void prefill_kernel(const PrefillProblem p)
         __syncthreads();
         tile_all<true>(p, lds, b, hq, i0, S);
     }
-    if (threadIdx.x == 0) p.tile_flags[flag_at] = flagged ? 1 : 0;
 }
 
 }  // namespace
@@ -404,7 +373,8 @@ hipError_t launch_prefill(const PrefillProblem &p, hipStream_t s)
     hipError_t e = launch(transpose_v_kernel, dim3(p.Spad / 64, p.B * p.Hkv), dim3(256), s, p);
     if (e != hipSuccess) return e;
     const long long groups8 = ((long long)p.B * p.Hkv + 7) / 8 * 8;
-    return launch(prefill_kernel, dim3((unsigned)(groups8 * p.G * p.tiles)), dim3(256), s, p);
+    const int qtiles = (p.Smax + kQTile - 1) / kQTile;
+    return launch(prefill_kernel, dim3((unsigned)(groups8 * p.G * qtiles)), dim3(256), s, p);
 }
 
 }  // namespace fd

@@ -1,29 +1,26 @@
 // Prompt (prefill) phase with the asynchronized softmax of Section 3: every token of a
 // prompt attends to itself and the tokens before it (Eq. 1 under the causal mask), all
-// weights taken against the unified scaling factor phi, so that partial sums over
-// disjoint key sets simply add (Eq. 4) -- here across the four wavefronts of a
-// workgroup, which split the keys of a 64-query tile between them and never exchange a
-// maximum.  A tile whose guard fires is redone on the spot with the synchronized
-// scheme (running maximum per query, Eq. 2 to merge the wavefronts).
+// weights taken against the unified scaling factor phi.  Partial sums over successive key
+// tiles then simply add (Eq. 4): no running maximum, and the output accumulators are never
+// rescaled while the keys stream by.  A 128-query tile whose guard fires is redone on the
+// spot with the synchronized scheme (running maximum per query, Eq. 2).
 //
 // Matrix-core mapping (16x16x32 MFMA; lane = (n, g) = (lane % 16, lane / 16)):
-//   scores   S^T[key][query] = K . Q^T      A = 16 keys of K straight from global memory
-//            (lane (n, g) fetches bytes 64 kb + 16 g .. +15 of its key's row), B = Q^T held
-//            in registers for the whole kernel.  Row 4g + r of key block t is key
+//   scores   S^T[key][query] = K . Q^T      A = 16 keys of the K tile in LDS, B = Q^T held in
+//            registers for the whole kernel.  Row 4g + r of key block t is key
 //            k0 + 8g + 4t + r: with that permutation the two score tiles of a 32-key
 //            step leave lane (n, g) holding keys k0 + 8g .. 8g + 7 of query n -- exactly
 //            the B operand of the second product, no data movement.
 //   weights  P = e^{s S^T - phi}, fp32, guard, causal mask.  fp16 cannot hold e^{x - phi}
 //            over the admissible range and bf16 has 8 significant bits, so P goes to the
-//            matrix cores as bf16 hi + lo (16 bits); the denominator sums hi + lo, the
-//            weight the products see.
+//            matrix cores as bf16 hi + lo (16 bits).
 //   output   O^T[d][query] = V^T . P^T       A = V^T from a transposed copy of V that a
-//            small pass writes first (keys contiguous per d: 16 bytes per lane, no LDS, no
-//            transposition in the loop), likewise split into bf16 hi + lo whose sum is the
-//            fp16 value exactly.  Three MFMAs per tile (Vh Ph + Vl Ph + Vh Pl) buy
-//            fp16-grade results from bf16 matrix cores.
-// No LDS and no barrier inside the key loop; LDS only carries the final sum over the
-// wavefronts.
+//            small pass writes first (keys contiguous per d, so the loop transposes
+//            nothing), likewise split into bf16 hi + lo whose sum is the fp16 value
+//            exactly.  Three MFMAs per tile (Vh Ph + Vl Ph + Vh Pl) buy fp16-grade results
+//            from bf16 matrix cores.
+// K and V^T tiles are fetched once per workgroup and shared by its four wavefronts through
+// double-buffered LDS (layouts free of bank conflicts for the 16-byte operand reads).
 #include "fd_chunk.h"
 
 namespace fd {
@@ -112,12 +109,14 @@ struct PrefillLds {
     int bad[4];
 };
 
-// K row r, 16-byte chunk c -> byte offset.  The 8 lanes that read together take rows
-// {0,1,2,3,8,9,10,11} (+4, +16, ...) of one chunk: XOR with (r & 3) | ((r >> 3) & 1) << 2 sends
-// them to 8 different 16-byte bank groups; a row's 16 chunks stay a permutation of themselves.
+// K row r, 16-byte chunk c -> byte offset.  The 16 lanes of one lane group read rows
+// {0..3, 8..11, 16..19, 24..27} (+4 for the second key block) of one chunk: XOR with
+// (r & 3) | ((r >> 3) & 3) << 2 sends them to 16 different 16-byte units of the 256-byte bank
+// window (and any aligned 8 of them to 8 different units of a 128-byte window); a row's 16
+// chunks stay a permutation of themselves, so the row-wise writes are conflict-free too.
 __device__ __forceinline__ int k_slot(int r, int c)
 {
-    return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 1) << 2))) << 4);
+    return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 3) << 2))) << 4);
 }
 
 template <bool ONLINE>
@@ -168,7 +167,10 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             const int id = tid + 256 * i;                // 512 chunks: K row r = id / 16, chunk c = id % 16
             const int r = id >> 4, c = id & 15;
             pk[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c);
-            const int d = id >> 2, gg = id & 3;          // V^T row d = id / 4, chunk gg = id % 4 (8 keys)
+            // V^T: 16 consecutive lanes take 16 consecutive rows d of one 8-key chunk gg (rows are 5
+            // 16-byte units apart in LDS: 16 different units); the 4 lane groups take the 4 chunks,
+            // so a wavefront still reads whole 64-byte pieces of 16 rows from global memory
+            const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
             const size_t at = (size_t)d * p.Spad + k0 + 8 * gg;
             ph[i] = *reinterpret_cast<const u32x4 *>(vh + at);
             pl[i] = *reinterpret_cast<const u32x4 *>(vl + at);
@@ -179,8 +181,9 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         for (int i = 0; i < 2; ++i) {
             const int id = tid + 256 * i;
             *reinterpret_cast<u32x4 *>(&lds.k[buf][k_slot(id >> 4, id & 15)]) = pk[i];
-            *reinterpret_cast<u32x4 *>(&lds.vh[buf][(id >> 2) * kVStride + 16 * (id & 3)]) = ph[i];
-            *reinterpret_cast<u32x4 *>(&lds.vl[buf][(id >> 2) * kVStride + 16 * (id & 3)]) = pl[i];
+            const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
+            *reinterpret_cast<u32x4 *>(&lds.vh[buf][d * kVStride + 16 * gg]) = ph[i];
+            *reinterpret_cast<u32x4 *>(&lds.vl[buf][d * kVStride + 16 * gg]) = pl[i];
         }
     };
     // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
@@ -260,18 +263,28 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         bf16x8 pB[2], pBl[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
-        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32 noise)
+        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32
+        // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run.
+        u32x4 a_hi[2], a_lo[2];
+        auto read_v = [&](int dt, int slot) {
+            const int off = (16 * dt + n) * kVStride + 16 * g;
+            a_hi[slot] = *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]);
+            a_lo[slot] = *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]);
+        };
+        read_v(0, 0);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            const int off = (16 * dt + n) * kVStride + 16 * g;
-            const bf16x8 a_hi = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]));
-            const bf16x8 a_lo = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]));
+            if (dt + 1 < 8) read_v(dt + 1, (dt + 1) & 1);
+            const bf16x8 vh8 = __builtin_bit_cast(bf16x8, a_hi[dt & 1]), vl8 = __builtin_bit_cast(bf16x8, a_lo[dt & 1]);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, pB[qb], acc[dt][qb], 0, 0, 0);
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, pB[qb], acc[dt][qb], 0, 0, 0);
-                acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, pBl[qb], acc[dt][qb], 0, 0, 0);
-            }
+            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pB[qb], acc[dt][qb], 0, 0, 0);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pB[qb], acc[dt][qb], 0, 0, 0);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBl[qb], acc[dt][qb], 0, 0, 0);
+            // keep the order: the next tile's two LDS reads, then this tile's six MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
         }
     };
 

@@ -302,7 +302,7 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
  * unified factor phi, partial sums over disjoint key sets added without a
  * maximum exchange, the range guard lo < x - phi < hi on every logit that takes
  * part, and on-the-spot recomputation with the synchronized scheme for a tile of
- * 64 queries whose guard fired.
+ * 128 queries in which the guard fired (flags are recorded per 64 queries).
  *   q, out   [batch, n_q_heads, max_seq, head_dim] fp16 (out is written)
  *   k_cache, v_cache [batch, n_kv_heads, max_seq, head_dim] fp16 (the prompt's keys)
  *   seq_lens [batch]: prompt length n_b = clamp(seq_lens[b], 0, max_seq); rows
@@ -321,7 +321,7 @@ fd_status fd_prefill_attn(const fd_shape *shape, const void *q, const void *k_ca
                           const int32_t *seq_lens, float phi, fd_bounds bounds, void *out,
                           fd_workspace ws, void *stream);
 /* Device pointer into `ws`: tile_flags [batch, n_q_heads, ceil(max_seq / 64)], 1 where
- * the guard fired for a logit of that 64-query tile (the tile was recomputed). */
+ * the guard fired for a logit of those 64 queries (their 128-query tile was recomputed). */
 fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uint8_t **tile_flags);
 
 /*

@@ -34,8 +34,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=640)
-    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="c1_b1_h32_s8192")
     ap.add_argument("--chunk", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV caches to cycle through (0 = auto)")

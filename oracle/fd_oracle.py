@@ -20,11 +20,16 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fd_oracle.c")
 _LIB = os.path.join(_HERE, "libfd_oracle.so")
+# FD_ORACLE_LIB points the loader at another build of the same interface: the mutation test
+# uses it to show that the pins reject oracles with planted mistakes.
+_OVERRIDE = os.environ.get("FD_ORACLE_LIB")
 _lib = None
 
 
 def build(force=False):
     """Compile fd_oracle.c with gcc into libfd_oracle.so next to it."""
+    if _OVERRIDE:
+        return _OVERRIDE
     if (not force and os.path.exists(_LIB)
             and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
         return _LIB
@@ -38,8 +43,7 @@ def build(force=False):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        L = ctypes.CDLL(_LIB)
+        L = ctypes.CDLL(build())
         c_i, c_f, c_p = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
         L.fdo_half_to_double.restype = ctypes.c_double
         L.fdo_half_to_double.argtypes = [ctypes.c_uint16]

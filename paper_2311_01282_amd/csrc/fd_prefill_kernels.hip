@@ -100,20 +100,26 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
 // (double-buffered, one barrier per step) and read from there by all four wavefronts as MFMA A
 // operands; Q^T stays in registers as the B operand.  Every output row belongs to one wavefront:
 // nothing is reduced across wavefronts, and with the unified phi nothing is ever rescaled.
+// A 16-byte LDS access of a wavefront is served 16 lanes per cycle, and the 16 are not
+// consecutive lanes: lanes 0-3, 12-15, 20-27 share a cycle, lanes 4-11, 16-19, 28-31 the next
+// (measured with a two-lane probe; likewise for the upper half).  In terms of lane = 16g + n a
+// cycle holds every n once, taken from two different g.  A layout is conflict-free when the
+// 16-byte unit (address / 16 mod 16) of lane (n, g) is a function of n alone and a permutation
+// of it (the V^T layout below), or n ^ g (the K layout).
 constexpr int kKStride = 256;    // bytes per K row in LDS (16 chunks of 16 bytes, XOR-swizzled)
-constexpr int kVStride = 80;     // bytes per V^T row (32 keys = 64 bytes, padded: rows 20 dwords apart)
 struct PrefillLds {
     alignas(16) unsigned char k[2][kStep * kKStride];          // 2 x 8 KiB
-    alignas(16) unsigned char vh[2][kHeadDim * kVStride];      // 2 x 10 KiB
-    alignas(16) unsigned char vl[2][kHeadDim * kVStride];      // 2 x 10 KiB
+    alignas(16) unsigned char vh[2][4 * kHeadDim * 16];        // 2 x 8 KiB: [8-key chunk g][d][16 bytes], unit = d % 16
+    alignas(16) unsigned char vl[2][4 * kHeadDim * 16];        // 2 x 8 KiB
     int bad[4];
 };
+// V^T: the 16 bytes of keys 8g .. 8g + 7 of row d
+__device__ __forceinline__ int v_slot(int d, int g) { return (g * kHeadDim + d) << 4; }
 
-// K row r, 16-byte chunk c -> byte offset.  The 16 lanes of one lane group read rows
-// {0..3, 8..11, 16..19, 24..27} (+4 for the second key block) of one chunk: XOR with
-// (r & 3) | ((r >> 3) & 3) << 2 sends them to 16 different 16-byte units of the 256-byte bank
-// window (and any aligned 8 of them to 8 different units of a 128-byte window); a row's 16
-// chunks stay a permutation of themselves, so the row-wise writes are conflict-free too.
+// K row r, 16-byte chunk c -> byte offset.  Lane (n, g) reads row r(n) in {0..3, 8..11, 16..19,
+// 24..27} (+4 for the second key block), chunk 4 kb + g: XOR with (r & 3) | ((r >> 3) & 3) << 2
+// (= n for those rows) puts it in unit (4 kb + g) ^ n; a row's 16 chunks stay a permutation of
+// themselves, so the row-wise writes are conflict-free too.
 __device__ __forceinline__ int k_slot(int r, int c)
 {
     return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 3) << 2))) << 4);
@@ -167,9 +173,8 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             const int id = tid + 256 * i;                // 512 chunks: K row r = id / 16, chunk c = id % 16
             const int r = id >> 4, c = id & 15;
             pk[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c);
-            // V^T: 16 consecutive lanes take 16 consecutive rows d of one 8-key chunk gg (rows are 5
-            // 16-byte units apart in LDS: 16 different units); the 4 lane groups take the 4 chunks,
-            // so a wavefront still reads whole 64-byte pieces of 16 rows from global memory
+            // V^T: 16 consecutive lanes take 16 consecutive rows d of one 8-key chunk gg, the 4 lane
+            // groups the 4 chunks, so a wavefront reads whole 64-byte pieces of 16 rows from global memory
             const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
             const size_t at = (size_t)d * p.Spad + k0 + 8 * gg;
             ph[i] = *reinterpret_cast<const u32x4 *>(vh + at);
@@ -182,8 +187,8 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             const int id = tid + 256 * i;
             *reinterpret_cast<u32x4 *>(&lds.k[buf][k_slot(id >> 4, id & 15)]) = pk[i];
             const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
-            *reinterpret_cast<u32x4 *>(&lds.vh[buf][d * kVStride + 16 * gg]) = ph[i];
-            *reinterpret_cast<u32x4 *>(&lds.vl[buf][d * kVStride + 16 * gg]) = pl[i];
+            *reinterpret_cast<u32x4 *>(&lds.vh[buf][v_slot(d, gg)]) = ph[i];
+            *reinterpret_cast<u32x4 *>(&lds.vl[buf][v_slot(d, gg)]) = pl[i];
         }
     };
     // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
@@ -267,7 +272,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run.
         u32x4 a_hi[2], a_lo[2];
         auto read_v = [&](int dt, int slot) {
-            const int off = (16 * dt + n) * kVStride + 16 * g;
+            const int off = v_slot(16 * dt + n, g);
             a_hi[slot] = *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]);
             a_lo[slot] = *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]);
         };

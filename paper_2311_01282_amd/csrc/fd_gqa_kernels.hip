@@ -134,9 +134,10 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         // Row i of the A operand is key pk = 4(i%4) + i/4 of the block, so that score
         // register r of lane group g belongs to key 4r + g -- the key whose V row the
         // same lane group fetched with load r (1 KiB contiguous per load).
-        // Swizzle key swz(r) = the two 2-bit halves of r swapped: the 16 rows a read touches
-        // get 16 different keys, and any 8 consecutive lanes get keys that differ modulo 8,
-        // so 16-byte accesses are conflict-free whether the LDS serves 8 or 16 lanes a cycle.
+        // Swizzle key swz(r) = the two 2-bit halves of r swapped: the read of lane (n, g) then
+        // lands in 16-byte unit (4 kb + g) ^ n, which is conflict-free on this chip (a 16-byte
+        // LDS access serves 16 lanes a cycle, every n once, from two lane groups g; measured:
+        // no conflict cycles).
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int r = 4 * i + g;

@@ -155,3 +155,21 @@ def test_calls_can_be_captured_in_a_graph_and_replayed(oracle, H):
             again = dc.run(entry)                        # eager work on the same workspace between replays
             assert np.array_equal(again, eager)
         del graph
+
+
+@pytest.mark.parametrize("chunk", [1024, 128])
+def test_long_context(oracle, H, chunk):
+    """128K keys per row: 128 chunks per row with the in-kernel hand-over (two levels of arrival
+    counters), 1024 chunks per row with the epilogue launch (its double-buffered loop)."""
+    case = synth.make_case(B=1, Hq=8, Hkv=8, D=128, Smax=131072, seq_lens=[131072 - 777], seed=9100)
+    want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=8)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, *synth.BOUNDS,
+                                    chunk, nthreads=8)
+    assert margin.min() > 1e-2
+    dc = H.DeviceCase(case, chunk=chunk)
+    got = dc.run("fd_decode_attn")
+    H.assert_close(got, want, "128K context, chunk %d" % chunk)
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+    got_sync = dc.run("fd_decode_attn_sync")
+    H.assert_close(got_sync, want, "128K context, synchronized scheme")

@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline and overflow A/B")
     ap.add_argument("--prefill", type=int, default=0, metavar="S",
                     help="time the prompt phase instead (fd_prefill_attn): batch 1, 32 heads, prompt of S tokens")
+    ap.add_argument("--prefill-heads", type=int, nargs=2, default=[32, 32], metavar=("HQ", "HKV"),
+                    help="query and KV heads of the --prefill workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run 8 plain device copies of 256 MiB (a kernel of known traffic, for scaling "
                          "hardware counters collected over this command)")
@@ -61,14 +63,16 @@ def prefill(args):
     from paper_2311_01282_amd import fdattn, synth
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    B, H, D, S = 1, 32, 128, args.prefill
+    B, D, S = 1, 128, args.prefill
+    H, Hkv = args.prefill_heads
     scale = float(np.float32(1.0 / np.sqrt(D)))
     gen = torch.Generator(device=dev)
     gen.manual_seed(6000 + S)
-    q, k, v = (torch.randn((B, H, S, D), generator=gen, device=dev, dtype=torch.float32).half() for _ in range(3))
+    q = torch.randn((B, H, S, D), generator=gen, device=dev, dtype=torch.float32).half()
+    k, v = (torch.randn((B, Hkv, S, D), generator=gen, device=dev, dtype=torch.float32).half() for _ in range(2))
     sl = torch.full((B,), S, dtype=torch.int32, device=dev)
     out = torch.empty_like(q)
-    shape = fdattn.make_shape(B, H, H, D, S, 0, scale)
+    shape = fdattn.make_shape(B, H, Hkv, D, S, 0, scale)
     nws = fdattn.fd_prefill_workspace_bytes(shape)
     ws = torch.empty(nws, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
@@ -109,8 +113,8 @@ def prefill(args):
         "metric": "prefill_attention_throughput", "value": round(flops / sec / 1e12, 1), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(sec * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "prefill_b1_h32_s%d" % S, "entry": "fd_prefill_attn", "batch": B, "n_q_heads": H,
-                   "n_kv_heads": H, "head_dim": D, "prompt": S, "causal": True, "phi": synth.PHI,
+        "config": {"workload": "prefill_b1_h%d%s_s%d" % (H, "" if H == Hkv else "x%d" % Hkv, S), "entry": "fd_prefill_attn",
+                   "batch": B, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": D, "prompt": S, "causal": True, "phi": synth.PHI,
                    "bounds": list(synth.BOUNDS), "kv_dtype": "f16", "launches_per_step": 2},
         "parity_max_abs_vs_oracle": max_abs,
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / sec / 1e12, 1),

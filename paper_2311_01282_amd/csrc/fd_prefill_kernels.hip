@@ -33,7 +33,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kQTile = 128;      // query rows per workgroup
+constexpr int kQB = 2;            // 16-query blocks per wavefront (1: 401, 2: 471-500 TFLOP/s at 8K)
+constexpr int kWaveQ = 16 * kQB;  // queries per wavefront
+constexpr int kQTile = 4 * kWaveQ; // query rows per workgroup
 constexpr int kStep = 32;        // keys per wavefront step
 
 // fp32 -> bf16 bit pattern, round to nearest even (finite inputs; NaN stays NaN).
@@ -138,30 +140,32 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     const uint16_t *vl = p.vt_lo + kv_head * kHeadDim * p.Spad;
     const float c1 = p.scale * kLog2e, c0 = -p.phi * kLog2e;      // log2 of e^{s x - phi} = c1 x + c0
     const float lo2 = p.lo * kLog2e, hi2 = p.hi * kLog2e;
-    const int w0 = i0 + 32 * wave;                       // first query of this wavefront
+    const int w0 = i0 + kWaveQ * wave;                       // first query of this wavefront
 
     // Q^T as the B operand: lane (n, g) holds d = 32 kb + 8g .. +7 of query w0 + 16 qb + n
-    f16x8 qB[2][4];
+    f16x8 qB[kQB][4];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < kQB; ++qb) {
         const int row = min(w0 + 16 * qb + n, p.Smax - 1);
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
             qB[qb][kb] = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(qbase + (size_t)row * kHeadDim + 32 * kb + 8 * g));
     }
-    f32x4 acc[8][2];
+    f32x4 acc[8][kQB];
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float den[2] = {0.f, 0.f}, mrun[2] = {-INFINITY, -INFINITY};
+        for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float den[kQB], mrun[kQB];
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) { den[qb] = 0.f; mrun[qb] = -INFINITY; }
     bool bad = false;
 
     // key steps: the workgroup walks 0 .. nsteps - 1 (keys some query of the tile sees); this
     // wavefront computes while a key of the step is visible to one of its queries
     const int last_q = min(i0 + kQTile, S) - 1;
     const int nsteps = last_q / kStep + 1;
-    const int my_last_q = min(w0 + 32, S) - 1;           // < w0 when the wavefront has no query
+    const int my_last_q = min(w0 + kWaveQ, S) - 1;           // < w0 when the wavefront has no query
     const int my_steps = my_last_q >= w0 ? my_last_q / kStep + 1 : 0;
 
     // cooperative tile fetch: thread t moves 2 chunks of K and 2 each of V^T hi / lo per step
@@ -249,9 +253,9 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         const int k0 = s * kStep;
         // scores: row m = n of key block t is key k0 + 8 (n >> 2) + 4t + (n & 3), so that the two
         // score tiles leave lane (n, g) holding keys k0 + 8g .. 8g + 7 of query n
-        f32x4 sc[2][2];
+        f32x4 sc[kQB][2];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
             for (int t = 0; t < 2; ++t) sc[qb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -261,13 +265,13 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             for (int kb = 0; kb < 4; ++kb) {
                 const f16x8 ka = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(&lds.k[buf][k_slot(r, 4 * kb + g)]));
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb)
+                for (int qb = 0; qb < kQB; ++qb)
                     sc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qB[qb][kb], sc[qb][t], 0, 0, 0);
             }
         }
-        bf16x8 pB[2], pBl[2];
+        bf16x8 pB[kQB], pBl[kQB];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
+        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
         // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32
         // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run.
         u32x4 a_hi[2], a_lo[2];
@@ -282,14 +286,14 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             if (dt + 1 < 8) read_v(dt + 1, (dt + 1) & 1);
             const bf16x8 vh8 = __builtin_bit_cast(bf16x8, a_hi[dt & 1]), vl8 = __builtin_bit_cast(bf16x8, a_lo[dt & 1]);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pB[qb], acc[dt][qb], 0, 0, 0);
+            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pB[qb], acc[dt][qb], 0, 0, 0);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pB[qb], acc[dt][qb], 0, 0, 0);
+            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pB[qb], acc[dt][qb], 0, 0, 0);
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBl[qb], acc[dt][qb], 0, 0, 0);
+            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBl[qb], acc[dt][qb], 0, 0, 0);
             // keep the order: the next tile's two LDS reads, then this tile's six MFMAs
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 3 * kQB, 0);
         }
     };
 
@@ -302,7 +306,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         if (s + 1 < nsteps) fetch(s + 1);                // uniform over the workgroup
         if (s < my_steps) {                              // uniform over the wavefront
             // steps entirely below this wavefront's first query, all 32 of whose queries exist, need no mask
-            if (s * kStep + kStep - 1 <= w0 && w0 + 32 <= S) compute(std::false_type{}, s, buf);
+            if (s * kStep + kStep - 1 <= w0 && w0 + kWaveQ <= S) compute(std::false_type{}, s, buf);
             else compute(std::true_type{}, s, buf);
         }
         if (s + 1 < nsteps) stash(buf ^ 1);              // last read in step s - 1, which every wavefront has left
@@ -310,7 +314,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     }
     // the four lane groups of a query hold disjoint keys: total per query
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < kQB; ++qb) {
         den[qb] += __shfl_xor(den[qb], 16);
         den[qb] += __shfl_xor(den[qb], 32);
     }
@@ -319,16 +323,19 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     __syncthreads();
     const bool flagged = (lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3]) != 0;
     if (!ONLINE) {
-        // one flag byte per 64 queries: wavefronts 0, 1 and 2, 3
-        if (tid == 0 || tid == 128) {
-            const int half = tid >> 7;
-            const int t64 = i0 / 64 + half;
-            if (t64 < p.tiles) p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + t64] = (lds.bad[2 * half] | lds.bad[2 * half + 1]) != 0;
+        // one flag byte per 64 queries
+        constexpr int kFlagTiles = kQTile / 64, kWavesPerFlag = 4 / kFlagTiles;
+        if (tid < kFlagTiles) {
+            const int t64 = i0 / 64 + tid;
+            int f = 0;
+#pragma unroll
+            for (int w = 0; w < kWavesPerFlag; ++w) f |= lds.bad[tid * kWavesPerFlag + w];
+            if (t64 < p.tiles) p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + t64] = f != 0;
         }
         if (flagged) return true;                        // uniform: the tile is redone, nothing stored
     }
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < kQB; ++qb) {
         const int row = w0 + 16 * qb + n;
         if (row >= p.Smax) continue;
         const bool live = row < S;
@@ -372,7 +379,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillProblem p)
         const int rows = min(kQTile, p.Smax - i0);
         for (int i = threadIdx.x; i < rows * (kHeadDim / 8); i += 256)
             reinterpret_cast<u32x4 *>(o)[i] = u32x4{0u, 0u, 0u, 0u};
-        if (threadIdx.x < 2 && i0 / 64 + (int)threadIdx.x < p.tiles)
+        if (threadIdx.x < kQTile / 64 && i0 / 64 + (int)threadIdx.x < p.tiles)
             p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + i0 / 64 + threadIdx.x] = 0;
         return;
     }

@@ -19,8 +19,9 @@
 //            nothing), likewise split into bf16 hi + lo whose sum is the fp16 value
 //            exactly.  Three MFMAs per tile (Vh Ph + Vl Ph + Vh Pl) buy fp16-grade results
 //            from bf16 matrix cores.
-// K and V^T tiles are fetched once per workgroup and shared by its four wavefronts through
-// double-buffered LDS (layouts free of bank conflicts for the 16-byte operand reads).
+// K and V^T tiles are loaded from global memory straight into LDS, once per workgroup, and
+// shared by its four wavefronts (double-buffered; layouts free of bank conflicts for the
+// 16-byte operand reads).
 #include "fd_chunk.h"
 
 namespace fd {
@@ -37,6 +38,7 @@ constexpr int kQB = 2;            // 16-query blocks per wavefront (1: 401, 2: 4
 constexpr int kWaveQ = 16 * kQB;  // queries per wavefront
 constexpr int kQTile = 4 * kWaveQ; // query rows per workgroup
 constexpr int kStep = 32;        // keys per wavefront step
+constexpr int kVAhead = 1;    // V^T operand tiles read from LDS ahead of the MFMAs that use them
 
 // fp32 -> bf16 bit pattern, round to nearest even (finite inputs; NaN stays NaN).
 __device__ __forceinline__ unsigned bf16_bits(float x)
@@ -47,7 +49,16 @@ __device__ __forceinline__ unsigned bf16_bits(float x)
 }
 __device__ __forceinline__ float bf16_value(unsigned bits) { return __builtin_bit_cast(float, bits << 16); }
 
-// ---- pass 0: V [B,Hkv,Smax,D] fp16 -> V^T hi/lo [B,Hkv,D,Spad] bf16, zero beyond the prompt ----
+// V^T of one KV head is stored tile by tile, in the order the attention kernel consumes it:
+// [32-key step][8-key chunk g][d][8 keys], so the 8 KiB a step needs are contiguous (whole
+// cache lines, and the image of the LDS tile).  Element offset of keys key .. key + 7 (key a
+// multiple of 8) of row d within the head:
+__device__ __forceinline__ size_t vt_offset(int key, int d)
+{
+    return (size_t)(key >> 5) * (32 * kHeadDim) + (size_t)((((key >> 3) & 3) * kHeadDim + d) << 3);
+}
+
+// ---- pass 0: V [B,Hkv,Smax,D] fp16 -> tiled V^T hi/lo (Spad keys) bf16, zero beyond the prompt ----
 __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p)
 {
     __shared__ float tile[64][kHeadDim + 1];
@@ -74,9 +85,10 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
         for (int j = 0; j < 8; ++j) tile[key][8 * c + j] = f[j];
     }
     __syncthreads();
-    // thread writes 8 keys of one d (16 bytes) to each of hi and lo, 4 times
+    // thread writes 8 keys of one d (16 bytes) to each of hi and lo, 4 times; consecutive threads
+    // take consecutive d, which are consecutive 16-byte pieces of the tiled layout
     for (int i = tid; i < kHeadDim * 8; i += 256) {
-        const int d = i >> 3, kc = i & 7;
+        const int d = i & (kHeadDim - 1), kc = i >> 7;
         unsigned hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -90,15 +102,23 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
             hi[j] = h2[0] | (h2[1] << 16);
             lo[j] = l2[0] | (l2[1] << 16);
         }
-        const size_t at = ((size_t)gi * kHeadDim + d) * p.Spad + k0 + 8 * kc;
+        const size_t at = (size_t)gi * kHeadDim * p.Spad + vt_offset(k0 + 8 * kc, d);
         *reinterpret_cast<u32x4 *>(p.vt_hi + at) = u32x4{hi[0], hi[1], hi[2], hi[3]};
         *reinterpret_cast<u32x4 *>(p.vt_lo + at) = u32x4{lo[0], lo[1], lo[2], lo[3]};
     }
 }
 
+// 16 bytes per lane from global memory into LDS without passing through registers: lane l's
+// bytes land at lds_base + 16 l (lds_base is the same for the whole wavefront).
+__device__ __forceinline__ void load_to_lds(const void *global, void *lds_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)global,
+                                     (__attribute__((address_space(3))) void *)lds_base, 16, 0, 0);
+}
+
 // ---- the attention kernel ----
 // A workgroup owns 128 queries of one head: wavefront w the 32 queries i0 + 32w .. +31 (two
-// blocks of 16).  The K and V^T tiles of a 32-key step are fetched once per workgroup into LDS
+// blocks of 16).  The K and V^T tiles of a 32-key step are loaded once per workgroup into LDS
 // (double-buffered, one barrier per step) and read from there by all four wavefronts as MFMA A
 // operands; Q^T stays in registers as the B operand.  Every output row belongs to one wavefront:
 // nothing is reduced across wavefronts, and with the unified phi nothing is ever rescaled.
@@ -159,7 +179,9 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     float den[kQB], mrun[kQB];
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) { den[qb] = 0.f; mrun[qb] = -INFINITY; }
-    bool bad = false;
+    float zlo[kQB], zhi[kQB];                                  // running extremes of log2 e^{x - phi} (guard)
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) { zlo[qb] = INFINITY; zhi[qb] = -INFINITY; }
 
     // key steps: the workgroup walks 0 .. nsteps - 1 (keys some query of the tile sees); this
     // wavefront computes while a key of the step is visible to one of its queries
@@ -168,33 +190,27 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     const int my_last_q = min(w0 + kWaveQ, S) - 1;           // < w0 when the wavefront has no query
     const int my_steps = my_last_q >= w0 ? my_last_q / kStep + 1 : 0;
 
-    // cooperative tile fetch: thread t moves 2 chunks of K and 2 each of V^T hi / lo per step
-    u32x4 pk[2], ph[2], pl[2];
-    auto fetch = [&](int s) {
+    // Cooperative tile fetch, global memory straight into LDS (no staging registers): a wavefront's
+    // load instruction fills 1 KiB of LDS, lane l the 16 bytes at l * 16 from the wavefront's base,
+    // each lane from a global address of its own.  Thread t moves chunks t and t + 256 of each of
+    // the K, V^T hi and V^T lo tiles.  The V^T tiles in memory are images of the LDS tiles; for K
+    // the lane whose LDS slot is (row r, physical chunk c') fetches logical chunk c' ^ key(r).
+    auto fetch = [&](int s, int buf) {
         const int k0 = s * kStep;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int id = tid + 256 * i;                // 512 chunks: K row r = id / 16, chunk c = id % 16
-            const int r = id >> 4, c = id & 15;
-            pk[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c);
-            // V^T: 16 consecutive lanes take 16 consecutive rows d of one 8-key chunk gg, the 4 lane
-            // groups the 4 chunks, so a wavefront reads whole 64-byte pieces of 16 rows from global memory
-            const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
-            const size_t at = (size_t)d * p.Spad + k0 + 8 * gg;
-            ph[i] = *reinterpret_cast<const u32x4 *>(vh + at);
-            pl[i] = *reinterpret_cast<const u32x4 *>(vl + at);
-        }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
             const int id = tid + 256 * i;
-            *reinterpret_cast<u32x4 *>(&lds.k[buf][k_slot(id >> 4, id & 15)]) = pk[i];
-            const int d = 16 * (id >> 6) + (id & 15), gg = (id >> 4) & 3;
-            *reinterpret_cast<u32x4 *>(&lds.vh[buf][v_slot(d, gg)]) = ph[i];
-            *reinterpret_cast<u32x4 *>(&lds.vl[buf][v_slot(d, gg)]) = pl[i];
+            const int base = (256 * i + 64 * wave) << 4;         // the wavefront's 1 KiB of each tile
+            const int r = id >> 4, c = (id & 15) ^ ((r & 3) | (((r >> 3) & 3) << 2));
+            const uint16_t *gk = kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c;
+            const size_t at = (size_t)s * (kStep * kHeadDim) + 8 * id;
+            load_to_lds(gk, &lds.k[buf][base]);
+            load_to_lds(vh + at, &lds.vh[buf][base]);
+            load_to_lds(vl + at, &lds.vl[buf][base]);
         }
     };
+    // the loads of this wavefront have landed in LDS
+    auto fetched = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
     auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2], bf16x8 &pB, bf16x8 &pBl, int k0) {
         constexpr bool MASKED = decltype(masked)::value;
@@ -204,23 +220,39 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][r], c1, c0);
-        float zmin, zmax;
-        if constexpr (MASKED) {
-            const int kmax = qrow < S ? qrow : -1;                   // last key this query sees
-            float zl[8];
+        float zmax = 0.f;
+        if constexpr (ONLINE) {
+            if constexpr (MASKED) {
+                const int kmax = qrow < S ? qrow : -1;                   // last key this query sees
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: key k0 + 8g + j
-                zl[j] = ok ? z[j] : INFINITY;
-                z[j] = ok ? z[j] : -INFINITY;                        // weight 0
+                for (int j = 0; j < 8; ++j) z[j] = k0 + 8 * g + j <= kmax ? z[j] : -INFINITY;   // weight 0
             }
-            zmin = fminf(fminf(fminf(zl[0], zl[1]), fminf(zl[2], zl[3])), fminf(fminf(zl[4], zl[5]), fminf(zl[6], zl[7])));
+            zmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
         } else {
-            zmin = fminf(fminf(fminf(z[0], z[1]), fminf(z[2], z[3])), fminf(fminf(z[4], z[5]), fminf(z[6], z[7])));
+            // Guard: running extremes of x - phi over all keys of the query, compared with the bounds
+            // once, after the last step (three-input min / max: four instructions each per block).
+            float zl[8];
+            if constexpr (MASKED) {
+                const int kmax = qrow < S ? qrow : -1;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: key k0 + 8g + j
+                    zl[j] = ok ? z[j] : INFINITY;
+                    z[j] = ok ? z[j] : -INFINITY;                        // weight 0
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) zl[j] = z[j];
+            }
+            float hi_run = zhi[qb], lo_run = zlo[qb];
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                hi_run = fmaxf(fmaxf(z[j], z[j + 1]), hi_run);
+                lo_run = fminf(fminf(zl[j], zl[j + 1]), lo_run);
+            }
+            zhi[qb] = hi_run;
+            zlo[qb] = lo_run;
         }
-        zmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-        // guard on the extremes (strict; a masked-out lane group has zmin = +inf, zmax = -inf)
-        bad |= (zmax >= hi2) | (zmin <= lo2);
         float shift = 0.f;
         if constexpr (ONLINE) {
             float m = zmax;
@@ -258,33 +290,38 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
             for (int t = 0; t < 2; ++t) sc[qb][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // all eight K operands of the step first (their LDS latency overlaps), then the MFMAs
+        u32x4 ka[2][4];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int r = 8 * (n >> 2) + 4 * t + (n & 3);
 #pragma unroll
-            for (int kb = 0; kb < 4; ++kb) {
-                const f16x8 ka = __builtin_bit_cast(f16x8, *reinterpret_cast<const u32x4 *>(&lds.k[buf][k_slot(r, 4 * kb + g)]));
+            for (int kb = 0; kb < 4; ++kb) ka[t][kb] = *reinterpret_cast<const u32x4 *>(&lds.k[buf][k_slot(r, 4 * kb + g)]);
+        }
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int qb = 0; qb < kQB; ++qb)
-                    sc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qB[qb][kb], sc[qb][t], 0, 0, 0);
-            }
-        }
-        bf16x8 pB[kQB], pBl[kQB];
-#pragma unroll
-        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
+                    sc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ka[t][kb]), qB[qb][kb], sc[qb][t], 0, 0, 0);
         // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32
-        // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run.
-        u32x4 a_hi[2], a_lo[2];
+        // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run;
+        // those of tile 0 before the weights are computed.
+        u32x4 a_hi[kVAhead + 1], a_lo[kVAhead + 1];
         auto read_v = [&](int dt, int slot) {
             const int off = v_slot(16 * dt + n, g);
             a_hi[slot] = *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]);
             a_lo[slot] = *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]);
         };
-        read_v(0, 0);
+#pragma unroll
+        for (int dt = 0; dt < kVAhead; ++dt) read_v(dt, dt);
+        bf16x8 pB[kQB], pBl[kQB];
+        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            if (dt + 1 < 8) read_v(dt + 1, (dt + 1) & 1);
-            const bf16x8 vh8 = __builtin_bit_cast(bf16x8, a_hi[dt & 1]), vl8 = __builtin_bit_cast(bf16x8, a_lo[dt & 1]);
+            if (dt + kVAhead < 8) read_v(dt + kVAhead, (dt + kVAhead) % (kVAhead + 1));
+            const bf16x8 vh8 = __builtin_bit_cast(bf16x8, a_hi[dt % (kVAhead + 1)]), vl8 = __builtin_bit_cast(bf16x8, a_lo[dt % (kVAhead + 1)]);
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pB[qb], acc[dt][qb], 0, 0, 0);
 #pragma unroll
@@ -297,19 +334,21 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         }
     };
 
-    fetch(0);
-    stash(0);
+    fetch(0, 0);
+    fetched();
     __syncthreads();
 #pragma unroll 1
     for (int s = 0; s < nsteps; ++s) {
         const int buf = s & 1;
-        if (s + 1 < nsteps) fetch(s + 1);                // uniform over the workgroup
+        // the other buffer was last read in step s - 1, which every wavefront has left
+        if (s + 1 < nsteps) fetch(s + 1, buf ^ 1);       // uniform over the workgroup
+        const bool full = s < my_steps && s * kStep + kStep - 1 <= w0 && w0 + kWaveQ <= S;
         if (s < my_steps) {                              // uniform over the wavefront
             // steps entirely below this wavefront's first query, all 32 of whose queries exist, need no mask
-            if (s * kStep + kStep - 1 <= w0 && w0 + kWaveQ <= S) compute(std::false_type{}, s, buf);
+            if (full) compute(std::false_type{}, s, buf);
             else compute(std::true_type{}, s, buf);
         }
-        if (s + 1 < nsteps) stash(buf ^ 1);              // last read in step s - 1, which every wavefront has left
+        fetched();
         __syncthreads();
     }
     // the four lane groups of a query hold disjoint keys: total per query
@@ -318,6 +357,10 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         den[qb] += __shfl_xor(den[qb], 16);
         den[qb] += __shfl_xor(den[qb], 32);
     }
+    // strict guard; a NaN logit (which the minimum and maximum skip) shows as a NaN denominator
+    bool bad = false;
+#pragma unroll
+    for (int qb = 0; qb < kQB; ++qb) bad |= (zhi[qb] >= hi2) | (zlo[qb] <= lo2) | (den[qb] != den[qb]);
     const unsigned long long any = __ballot(bad);
     if (lane == 0) lds.bad[wave] = any != 0ull;
     __syncthreads();

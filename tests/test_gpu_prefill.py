@@ -125,6 +125,26 @@ def test_flagged_tiles_are_recomputed(H):
     H.assert_close(got.reshape(-1, 128), want, "prefill with recomputation")
 
 
+def test_nan_logit_flags_its_tiles(H):
+    # a NaN inside a key of the prompt makes every logit against it NaN: the guard flags those
+    # rows (a NaN is outside every range); rows before the key, and other heads, are untouched
+    B, Hq, Hkv, Smax = 1, 2, 2, 256
+    q, k, v, sl = draw(B, Hq, Hkv, Smax, [230], seed=7400)
+    scale = float(np.float32(1.0 / np.sqrt(128.0)))
+    k[0, 1, 70, 5] = np.float16(np.nan)
+    rows = pf.all_rows(B, Hq, Smax)
+    want, flag, _ = pf.prefill_rows(q, k, v, sl, scale, rows, phi=synth.PHI, lo=LO, hi=HI, nthreads=8)
+    want_tf = tile_flags_from_rows(rows, flag, B, Hq, Smax)
+    assert want_tf[0, 0].sum() == 0 and want_tf[0, 1].tolist() == [0, 1, 1, 1]
+    got, tf = run_gpu(q, k, v, sl, scale)
+    assert np.array_equal(tf, want_tf)
+    got = got.reshape(-1, 128)
+    clean = np.isfinite(want).all(axis=1)
+    assert clean.sum() == Smax + 70 + (Smax - 230)      # head 0, head 1 before the key, rows past the prompt
+    H.assert_close(got[clean], want[clean], "prefill rows that do not see the NaN key")
+    assert np.isnan(got[~clean]).all()
+
+
 def test_lower_bound_flags_too(H):
     # phi far above the logits: every logit is below phi + lo, every tile with a token is flagged,
     # and the synchronized scheme still gives the exact result

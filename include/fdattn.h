@@ -311,8 +311,9 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
  * bytes, 256-byte aligned, arbitrary previous contents (it receives a transposed
  * bf16 hi/lo copy of V and one flag byte per (row head, 64-query tile)); no
  * initialisation call is needed.  Arithmetic: fp16 products with fp32 accumulation
- * for the scores, fp32 exponentials rounded to bf16 for the weights (the
- * denominator sums the rounded weights), V exact as bf16 hi + lo.
+ * for the scores; fp32 exponentials, which enter the second product as bf16 hi + lo
+ * pairs (16 significant bits; the denominator sums the fp32 values); V exact as
+ * bf16 hi + lo.  As in decode, equality with a bound flags, and so does a NaN logit.
  * Errors as for fd_decode_attn; FD_ERR_UNSUPPORTED beyond 65535 heads, sequences
  * or batch * n_kv_heads.
  */

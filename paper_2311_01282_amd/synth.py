@@ -113,3 +113,37 @@ def plant_keys(case, n_rows, gamma, seed, allow_shared_kv=False):
         case["k"][b, h // G, pos, :] = (gamma * qv / np.linalg.norm(qv)).astype(np.float16)
         planted.append((b, h, pos))
     return planted
+
+
+def to_pages(case, page_size, seed, spare_pages=3, poison_unused=True):
+    """Lay a drawn case's K and V out as a paged cache.
+
+    Returns (k_pool, v_pool, table): pools ``[n_pages, Hkv, page_size, D]`` float16 and
+    ``table [B, Smax / page_size]`` int32.  The pages that hold valid tokens get distinct,
+    seeded-random places in the pool; table entries of pages without a valid token are -1;
+    pool pages nobody uses (``spare_pages`` extra ones, and the unused tail of the last page
+    of a sequence when ``poison_unused``) hold NaN, so a test can prove they are never read.
+    Only copies bytes: no attention arithmetic here.
+    """
+    k, v, sl = case["k"], case["v"], case["seq_lens"]
+    B, Hkv, Smax, D = k.shape
+    P = int(page_size)
+    if Smax % P:
+        raise ValueError("Smax must be a multiple of the page size")
+    T = Smax // P
+    used = [(b, j) for b in range(B) for j in range((int(np.clip(sl[b], 0, Smax)) + P - 1) // P)]
+    n_pages = len(used) + spare_pages
+    rng = np.random.default_rng(seed)
+    place = rng.permutation(n_pages)[:len(used)]
+    k_pool = np.full((n_pages, Hkv, P, D), np.float16(np.nan), dtype=np.float16)
+    v_pool = np.full((n_pages, Hkv, P, D), np.float16(np.nan), dtype=np.float16)
+    table = np.full((B, T), -1, dtype=np.int32)
+    for (b, j), pid in zip(used, place):
+        k_pool[pid] = k[b, :, j * P:(j + 1) * P, :]
+        v_pool[pid] = v[b, :, j * P:(j + 1) * P, :]
+        table[b, j] = pid
+        n = int(np.clip(sl[b], 0, Smax))
+        if poison_unused and (j + 1) * P > n:
+            k_pool[pid, :, n - j * P:, :] = np.float16(np.nan)
+            v_pool[pid, :, n - j * P:, :] = np.float16(np.nan)
+    return k_pool, v_pool, table

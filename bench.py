@@ -280,8 +280,8 @@ def main():
     # ---- dominant kernel alone, HIP events on the launch stream ----
     roofline = None
     if entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
-        kname = ("decode_fused_gqa_kernel<%d>" % chunk if entry == "fd_decode_attn_gqa" else
-                 "decode_fused_kernel<%d, %s>" % (chunk, "true" if run.single_launch else "false"))
+        kname = ("decode_fused_gqa_kernel<%d, false>" % chunk if entry == "fd_decode_attn_gqa" else
+                 "decode_fused_kernel<%d, %s, false>" % (chunk, "true" if run.single_launch else "false"))
         k_sec = events(run.step if run.single_launch else run.chunk_kernel, args.steps, args.warmup)
         achieved = kv_bytes / k_sec / 1e9
         roofline = {"bound": "hbm", "kernel": kname,
@@ -361,6 +361,39 @@ def main():
                                   "us_without": round(t_without * 1e6, 2),
                                   "overhead_pct": round(100.0 * (t_with / t_without - 1.0), 2),
                                   "overhead_one_row_pct": round(100.0 * (t_one / t_without - 1.0), 2)}
+
+    if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
+        # the same step over a paged cache: every layer's K and V cut into pages that sit at
+        # seeded-random places of a pool (fd_decode_attn_paged); pages of 16 and of 256 tokens
+        paged = {}
+        for page in (16, 256):
+            if Smax % page or chunk > 64 * page:
+                continue
+            T = Smax // page
+            perm = torch.randperm(B * T, generator=gen, device=dev)
+            table = perm.view(B, T).to(torch.int32).contiguous()
+            def pool(t):
+                pages = t.view(B, Hkv, T, page, D).permute(0, 2, 1, 3, 4).reshape(B * T, Hkv, page, D)
+                out_pool = torch.empty((B * T, Hkv, page, D), dtype=t.dtype, device=dev)     # contiguous, whatever `pages` is
+                out_pool[perm] = pages
+                return out_pool
+            kps, vps = [pool(t) for t in ks], [pool(t) for t in vs]
+            def step_paged(i):
+                l = i % layers
+                fdattn.fd_decode_attn_paged(run.shape, qs[l].data_ptr(), kps[l].data_ptr(), vps[l].data_ptr(), table.data_ptr(),
+                                            page, B * T, seq_lens.data_ptr(), phi, bounds, out.data_ptr(),
+                                            run.ws.data_ptr(), run.ws_bytes, stream)
+            run.step(0)
+            torch.cuda.synchronize()
+            ref = out.clone()
+            step_paged(0)
+            torch.cuda.synchronize()
+            if not torch.allclose(out.float(), ref.float(), rtol=0.0, atol=1e-3):
+                print("bench.py: paged result differs from the contiguous one", file=sys.stderr)
+                return 1
+            paged[str(page)] = round(wall(step_paged, short, 10) * 1e6, 2)
+            del kps, vps
+        extras["paged_us"] = paged
 
     if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # the same step with the cache update fused in: one key fewer in the cache, the step's own

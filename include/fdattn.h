@@ -164,6 +164,29 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
                                 fd_bounds bounds, void *out, fd_workspace ws, void *stream);
 
 /*
+ * fd_decode_attn / fd_decode_attn_gqa over a paged cache.  The paper keeps each
+ * sequence's keys and values concatenated (Section 2.1) and does not say where in
+ * memory; here they sit in fixed-size pages that need not be adjacent:
+ *   k_pool, v_pool [n_pages, n_kv_heads, page_size, head_dim] fp16
+ *   block_table    [batch, max_seq / page_size] int32 (device): token t of sequence b
+ *                  is row t % page_size of page block_table[b][t / page_size].
+ * shape->max_seq is the logical capacity per sequence, a multiple of page_size;
+ * page_size is a power of two >= 16 with shape->chunk <= 64 * page_size.  Only the
+ * entries of pages that hold a valid token (t < seq_lens[b]) are followed; the
+ * others may hold anything (they are clamped into [0, n_pages) and what they bring
+ * in is never used); an entry of a page in use that is out of range is the
+ * caller's error and reads the wrong page.  Chunks, flags, recomputation,
+ * workspace, the fd_workspace_init requirement and errors are those of
+ * fd_decode_attn; chunk c covers tokens cC .. (c+1)C - 1 whatever pages hold them.
+ * Grouped shapes (2 <= n_q_heads / n_kv_heads <= 16) take the grouped kernel.
+ * FD_ERR_SHAPE for a page_size or n_pages outside the stated limits.
+ */
+fd_status fd_decode_attn_paged(const fd_shape *shape, const void *q, const void *k_pool, const void *v_pool,
+                               const int32_t *block_table, int32_t page_size, int32_t n_pages,
+                               const int32_t *seq_lens, float phi, fd_bounds bounds, void *out,
+                               fd_workspace ws, void *stream);
+
+/*
  * The same method as a chain of five small-step kernels with no atomics at all,
  * following Section 3 to the letter:
  *   1. per (row, chunk): Eq. 4 inner sums and the range guard;

@@ -163,16 +163,50 @@ __device__ __forceinline__ int seq_len_finish(const Problem &p, int raw)
     return clamp_len(p, __builtin_amdgcn_readfirstlane(raw));     // resident keys
 }
 
+// Where the rows of a chunk's keys are, in 16-byte units from the start of K (or V; both are
+// laid out alike): consecutive rows of the caller's buffer, or -- paged cache -- row t % page of
+// the page the sequence's table names for t / page.  A chunk spans at most 64 pages (the
+// entry points see to it); each lane fetches one table entry when the chunk starts and a lane
+// exchange hands every lane the page of the key it is about to load.  Entries of pages that
+// hold no valid key may be anything: they are clamped into the pool and what they bring in is
+// never used.
+template <bool PAGED> struct KvRows {
+    size_t base;             // first row of the chunk (contiguous), 0 (paged)
+    int pages, first, start, shift, hkv, Hkv;
+    __device__ __forceinline__ KvRows(const Problem &p, int b, int hkv_, int start_, int lane)
+        : base(PAGED ? 0 : (((size_t)b * p.Hkv + hkv_) * p.Smax + start_) * 16), pages(0), first(0), start(start_),
+          shift(p.page_shift), hkv(hkv_), Hkv(p.Hkv)
+    {
+        if constexpr (PAGED) {
+            first = start_ >> shift;
+            const int entry = p.block_table[(size_t)b * p.pages_per_seq + min(first + lane, p.pages_per_seq - 1)];
+            pages = min(max(entry, 0), p.n_pages - 1);
+        }
+    }
+    // row of chunk-relative key `key`, relative to `base`
+    __device__ __forceinline__ size_t operator()(int key) const
+    {
+        if constexpr (PAGED) {
+            const int t = start + key;
+            const int page = __builtin_amdgcn_ds_bpermute(((t >> shift) - first) << 2, pages);
+            return ((((size_t)page * Hkv + hkv) << shift) + (size_t)(t & ((1 << shift) - 1))) * 16;
+        } else {
+            return (size_t)key * 16;
+        }
+    }
+};
+
 // EARLY (unified scheme only): the first block's loads are issued before the
 // sequence length has arrived, clamped to the chunk's extent in the padded buffer
 // instead of to the last valid key; what they bring in from beyond the valid
 // length is replaced by zeros before use.  Takes the length load off the critical
 // path of a short launch; a padding chunk then reads one block for nothing, so
 // large ragged launches leave it off.
-template <int C, int NW, int UP, bool SYNC, int XN, bool EARLY = false>
+template <int C, int NW, int UP, bool SYNC, int XN, bool EARLY = false, bool PAGED = false>
 __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds, int *len_out = nullptr)
 {
     static_assert(!(EARLY && SYNC), "early loads belong to the unified scheme");
+    static_assert(!(EARLY && PAGED), "the page table has to arrive before the first load");
     static_assert(!SYNC || XN >= C, "the synchronized scheme keeps the chunk's logits in LDS");
     constexpr int NG = C / (4 * NW);           // groups of 4 keys each wavefront handles
     static_assert(NG >= 1 && NG % UP == 0, "chunk, wavefront count and stage depth must divide");
@@ -190,18 +224,18 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     const size_t slot = (size_t)row * p.nc + c;
 
     const u32x4 qv = reinterpret_cast<const u32x4 *>(p.q + (size_t)row * kHeadDim)[seg];
-    const size_t kv_off = (((size_t)b * p.Hkv + hkv) * p.Smax + start) * kHeadDim;
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + seg;
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + seg;
+    const KvRows<PAGED> at(p, b, hkv, start, lane);
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k) + at.base + seg;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v) + at.base + seg;
     // key handled by this lane in group g of the chunk: the NW wavefronts interleave
     auto key_of = [&](int g) { return (g * NW + wave) * 4 + sub; };
     u32x4 kA[UP], vA[UP];
     if constexpr (EARLY) {
         const int cap = min(C, p.Smax - start) - 1;   // the chunk's last key inside the buffer (start < Smax)
 #pragma unroll
-        for (int u = 0; u < UP; ++u) kA[u] = load_stream(kp + (size_t)min(key_of(u), cap) * 16);
+        for (int u = 0; u < UP; ++u) kA[u] = load_stream(kp + at(min(key_of(u), cap)));
 #pragma unroll
-        for (int u = 0; u < UP; ++u) vA[u] = load_stream(vp + (size_t)min(key_of(u), cap) * 16);
+        for (int u = 0; u < UP; ++u) vA[u] = load_stream(vp + at(min(key_of(u), cap)));
     }
 
     if constexpr (EARLY) __builtin_amdgcn_sched_barrier(0);   // the loads above go out before the length is awaited
@@ -245,9 +279,9 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         bool bad = false;
         auto issue = [&](int blk, u32x4 (&kk)[UP], u32x4 (&vv)[UP]) {
 #pragma unroll
-            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)min(key_of(blk * UP + u), last) * 16);
+            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + at(min(key_of(blk * UP + u), last)));
 #pragma unroll
-            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)min(key_of(blk * UP + u), last) * 16);
+            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + at(min(key_of(blk * UP + u), last)));
         };
         auto reduce = [&](int blk, const u32x4 (&kk)[UP], const u32x4 (&vv)[UP]) {
 #pragma unroll
@@ -270,9 +304,9 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
             // blocks in flight; loads past the last block re-read the last valid key.
             if constexpr (NBLK > 1) {
 #pragma unroll
-                for (int u = 0; u < UP; ++u) kB[u] = load_stream(kp + (size_t)max(min(key_of(UP + u), last), 0) * 16);
+                for (int u = 0; u < UP; ++u) kB[u] = load_stream(kp + at(max(min(key_of(UP + u), last), 0)));
 #pragma unroll
-                for (int u = 0; u < UP; ++u) vB[u] = load_stream(vp + (size_t)max(min(key_of(UP + u), last), 0) * 16);
+                for (int u = 0; u < UP; ++u) vB[u] = load_stream(vp + at(max(min(key_of(UP + u), last), 0)));
             }
 #pragma unroll
             for (int u = 0; u < UP; ++u)
@@ -342,7 +376,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int blk = 0; blk < nblk_all; ++blk) {
             u32x4 kk[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + (size_t)max(min(key_of(blk * UP + u), last), 0) * 16);
+            for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + at(max(min(key_of(blk * UP + u), last), 0)));
 #pragma unroll
             for (int u = 0; u < UP; ++u) {
                 const int kidx = key_of(blk * UP + u);
@@ -365,7 +399,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int blk = 0; blk < nblk_all; ++blk) {
             u32x4 vv[UP];
 #pragma unroll
-            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + (size_t)max(min(key_of(blk * UP + u), last), 0) * 16);
+            for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + at(max(min(key_of(blk * UP + u), last), 0)));
 #pragma unroll
             for (int u = 0; u < UP; ++u) {
                 const int kidx = key_of(blk * UP + u);

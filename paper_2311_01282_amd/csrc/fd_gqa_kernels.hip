@@ -58,7 +58,7 @@ __device__ __forceinline__ void cvt8(const u32x4 &v, float (&o)[8])
     }
 }
 
-template <int C>
+template <int C, bool PAGED = false>
 __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const Problem p)
 {
     static_assert(sizeof(ChunkLds<4, C>) <= sizeof(float) * kTileFloats, "recompute workspace must fit the tile");
@@ -106,9 +106,9 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         qb[kb] = __builtin_bit_cast(f16x8, t);
     }
 
-    const size_t kv_off = ((size_t)gi * p.Smax + start) * kHeadDim;
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k + kv_off) + n;
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v + kv_off) + n;
+    const KvRows<PAGED> at(p, b, gi - b * p.Hkv, start, lane);   // rows of the chunk's keys (contiguous or paged)
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k) + at.base + n;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v) + at.base + n;
     const int last = nres - 1;                 // last resident key; the appended one joins at the reduction
     const float nphi = -p.phi, lo = p.lo, hi = p.hi, scale = p.scale;
     u32x4 *kst = reinterpret_cast<u32x4 *>(lds.tile) + wave * 256;     // this wavefront's 16 x 16 slots
@@ -124,9 +124,9 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     auto issue = [&](int blk, u32x4 (&kk)[4], u32x4 (&vv)[4]) {
         const int k0 = blk * 16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + (size_t)min(k0 + 4 * i + g, last) * 16);
+        for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + at(min(k0 + 4 * i + g, last)));
 #pragma unroll
-        for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + (size_t)min(k0 + 4 * r + g, last) * 16);
+        for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + at(min(k0 + 4 * r + g, last)));
     };
     auto reduce = [&](int blk, const u32x4 (&kk)[4], const u32x4 (&vv)[4]) {
         const int k0 = blk * 16;
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         for (int h = 0; h < G; ++h) {
             if (!((flagged_heads >> h) & 1)) continue;
             __syncthreads();
-            chunk_body<C, 4, (C / 16 < 8 ? C / 16 : 8), true>(p, row0 + h, c, *reinterpret_cast<ChunkLds<4, C> *>(lds.tile));
+            chunk_body<C, 4, (C / 16 < 8 ? C / 16 : 8), true, C, false, PAGED>(p, row0 + h, c, *reinterpret_cast<ChunkLds<4, C> *>(lds.tile));
         }
     }
 
@@ -309,6 +309,7 @@ template <int C> struct GqaLauncher {
         const long long groups = (long long)p.B * p.Hkv;
         const unsigned grid = (unsigned)(8ll * ((groups + 7) / 8) * p.nc);
         if (grid == 0) return hipSuccess;
+        if (p.block_table) return launch(decode_fused_gqa_kernel<C, true>, dim3(grid), dim3(kGqaThreads), s, p);
         return launch(decode_fused_gqa_kernel<C>, dim3(grid), dim3(kGqaThreads), s, p);
     }
 };

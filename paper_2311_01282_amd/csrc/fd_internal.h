@@ -47,6 +47,11 @@ struct Problem {
     // written into the cache through k_store / v_store (the cache pointers, writable).
     const uint16_t *k_new, *v_new;
     uint16_t *k_store, *v_store;
+    // Paged cache (null otherwise): k and v are then pools [n_pages, Hkv, page, D] and token t of
+    // sequence b lives in row t % page of page block_table[b * pages_per_seq + t / page];
+    // page = 1 << page_shift.  Smax is the logical capacity pages_per_seq * page.
+    const int32_t *block_table;
+    int pages_per_seq, page_shift, n_pages;
 };
 
 // Number of keys resident in the cache: the clamped entry of seq_lens.

@@ -25,7 +25,8 @@ template <int C> struct Tune {
 };
 
 // ELECT: the launch is small enough for the in-kernel hand-over (and for early loads).
-template <int C, bool ELECT>
+// PAGED: K and V are page pools addressed through the sequence's block table.
+template <int C, bool ELECT, bool PAGED = false>
 __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Problem p)
 {
     constexpr int NW = Tune<C>::NW, UP = Tune<C>::UP;
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     const int row = (blockIdx.x & 7) + 8 * (j / p.nc), c = j % p.nc;
     if (row >= p.rows) return;
     int S;
-    const bool flagged = chunk_body<C, NW, UP, false, C, ELECT>(p, row, c, lds, &S);
+    const bool flagged = chunk_body<C, NW, UP, false, C, ELECT && !PAGED, PAGED>(p, row, c, lds, &S);
     const int nb = (S + C - 1) / C;            // chunks of this row that hold a valid key
     if (c >= nb) {                             // padding chunk: zero partials were written
         if (nb == 0 && c == 0 && ELECT) {    // empty sequence: nobody else owns the row
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     }
     if (flagged) {                             // Section 3 "Recomputation", for this partial vector
         __syncthreads();
-        chunk_body<C, NW, UP, true>(p, row, c, lds);
+        chunk_body<C, NW, UP, true, C, false, PAGED>(p, row, c, lds);
     }
 
     if (!ELECT) return;                        // a row-epilogue launch follows
@@ -115,6 +116,9 @@ template <int C> struct FusedLauncher {
     {
         const unsigned grid = (unsigned)(8ll * ((p.rows + 7) / 8) * p.nc);
         if (grid == 0) return hipSuccess;
+        if (p.block_table)
+            return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
+                           : launch(decode_fused_kernel<C, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
         return p.elect ? launch(decode_fused_kernel<C, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                        : launch(decode_fused_kernel<C, false>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
     }

@@ -365,7 +365,7 @@ def main():
     if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # the same step over a paged cache: every layer's K and V cut into pages that sit at
         # seeded-random places of a pool (fd_decode_attn_paged); pages of 16 and of 256 tokens
-        paged = {}
+        paged, paged_append = {}, {}
         for page in (16, 256):
             if Smax % page or chunk > 64 * page:
                 continue
@@ -392,8 +392,19 @@ def main():
                 print("bench.py: paged result differs from the contiguous one", file=sys.stderr)
                 return 1
             paged[str(page)] = round(wall(step_paged, short, 10) * 1e6, 2)
+            # ... and with the cache update fused in (one key fewer resident; the rows go into their page)
+            lens_p = torch.clamp(seq_lens - 1, min=0)
+            kn_p = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+            vn_p = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+            def step_paged_append(i):
+                l = i % layers
+                fdattn.fd_decode_attn_paged_append(run.shape, qs[l].data_ptr(), kn_p.data_ptr(), vn_p.data_ptr(), kps[l].data_ptr(),
+                                                   vps[l].data_ptr(), table.data_ptr(), page, B * T, lens_p.data_ptr(), phi, bounds,
+                                                   out.data_ptr(), run.ws.data_ptr(), run.ws_bytes, stream)
+            paged_append[str(page)] = round(wall(step_paged_append, short, 10) * 1e6, 2)
             del kps, vps
         extras["paged_us"] = paged
+        extras["paged_append_us"] = paged_append
 
     if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # the same step with the cache update fused in: one key fewer in the cache, the step's own

@@ -187,6 +187,21 @@ fd_status fd_decode_attn_paged(const fd_shape *shape, const void *q, const void 
                                fd_workspace ws, void *stream);
 
 /*
+ * fd_decode_attn_append over a paged cache: the step's rows k_new, v_new
+ * [batch, n_kv_heads, head_dim] are attended from their own buffers and written to
+ * row n % page_size of page block_table[b][n / page_size], n = clamp(seq_lens[b], 0,
+ * max_seq), by the same launch.  That entry of the table must name the page the
+ * caller has set aside for the token (a fresh page when n is a multiple of
+ * page_size); it is followed although the page holds no valid token yet.  A full
+ * sequence (n == max_seq) drops the rows.  Everything else as fd_decode_attn_paged
+ * and fd_decode_attn_append.
+ */
+fd_status fd_decode_attn_paged_append(const fd_shape *shape, const void *q, const void *k_new, const void *v_new,
+                                      void *k_pool, void *v_pool, const int32_t *block_table, int32_t page_size,
+                                      int32_t n_pages, const int32_t *seq_lens, float phi, fd_bounds bounds,
+                                      void *out, fd_workspace ws, void *stream);
+
+/*
  * The same method as a chain of five small-step kernels with no atomics at all,
  * following Section 3 to the letter:
  *   1. per (row, chunk): Eq. 4 inner sums and the range guard;

@@ -298,6 +298,35 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
     return FD_OK;
 }
 
+// Shared by the two paged entry points: checks and fields of the paged cache.
+static fd_status set_paged(fd::Problem *p, const fd_shape *shape, const int32_t *block_table, int32_t page_size, int32_t n_pages)
+{
+    if (!block_table) return FD_ERR_NULL;
+    if (((uintptr_t)block_table % 4) != 0) return FD_ERR_SHAPE;
+    // a power of two; a chunk may span at most 64 pages (one table entry per lane)
+    if (page_size < 16 || (page_size & (page_size - 1)) != 0 || n_pages < 1 || shape->max_seq % page_size != 0 ||
+        shape->chunk > 64 * (long long)page_size)
+        return FD_ERR_SHAPE;
+    p->block_table = block_table;
+    p->pages_per_seq = shape->max_seq / page_size;
+    p->page_shift = __builtin_ctz((unsigned)page_size);
+    p->n_pages = n_pages;
+    return FD_OK;
+}
+
+static fd_status run_fused(fd::Problem &p, hipStream_t s)
+{
+    if (p.G >= 2 && p.G <= 16) {
+        p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
+        FD_TRY(fd::launch_decode_fused_gqa(p, s));
+    } else {
+        p.elect = elect_in_kernel((long long)p.rows * p.nc);
+        FD_TRY(fd::launch_decode_fused(p, s));
+    }
+    if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
+    return FD_OK;
+}
+
 fd_status fd_decode_attn_paged(const fd_shape *shape, const void *q, const void *k_pool, const void *v_pool,
                                const int32_t *block_table, int32_t page_size, int32_t n_pages,
                                const int32_t *seq_lens, float phi, fd_bounds bounds, void *out,
@@ -308,27 +337,32 @@ fd_status fd_decode_attn_paged(const fd_shape *shape, const void *q, const void 
     if (st != FD_OK) return st;
     st = set_guard(&p, phi, bounds);
     if (st != FD_OK) return st;
-    if (!block_table) return FD_ERR_NULL;
-    if (((uintptr_t)block_table % 4) != 0) return FD_ERR_SHAPE;
-    // a power of two; a chunk may span at most 64 pages (one table entry per lane)
-    if (page_size < 16 || (page_size & (page_size - 1)) != 0 || n_pages < 1 || shape->max_seq % page_size != 0 ||
-        shape->chunk > 64 * (long long)page_size)
-        return FD_ERR_SHAPE;
+    st = set_paged(&p, shape, block_table, page_size, n_pages);
+    if (st != FD_OK) return st;
     if (p.rows == 0) return FD_OK;
-    p.block_table = block_table;
-    p.pages_per_seq = shape->max_seq / page_size;
-    p.page_shift = __builtin_ctz((unsigned)page_size);
-    p.n_pages = n_pages;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (p.G >= 2 && p.G <= 16) {
-        p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
-        FD_TRY(fd::launch_decode_fused_gqa(p, s));
-    } else {
-        p.elect = elect_in_kernel((long long)p.rows * p.nc);
-        FD_TRY(fd::launch_decode_fused(p, s));
-    }
-    if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
-    return FD_OK;
+    return run_fused(p, static_cast<hipStream_t>(stream));
+}
+
+fd_status fd_decode_attn_paged_append(const fd_shape *shape, const void *q, const void *k_new, const void *v_new,
+                                      void *k_pool, void *v_pool, const int32_t *block_table, int32_t page_size,
+                                      int32_t n_pages, const int32_t *seq_lens, float phi, fd_bounds bounds,
+                                      void *out, fd_workspace ws, void *stream)
+{
+    fd::Problem p;
+    fd_status st = make_problem(shape, q, k_pool, v_pool, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    st = set_paged(&p, shape, block_table, page_size, n_pages);
+    if (st != FD_OK) return st;
+    if (!k_new || !v_new) return FD_ERR_NULL;
+    if (misaligned(k_new) || misaligned(v_new)) return FD_ERR_SHAPE;
+    if (p.rows == 0) return FD_OK;
+    p.k_new = static_cast<const uint16_t *>(k_new);
+    p.v_new = static_cast<const uint16_t *>(v_new);
+    p.k_store = static_cast<uint16_t *>(k_pool);
+    p.v_store = static_cast<uint16_t *>(v_pool);
+    return run_fused(p, static_cast<hipStream_t>(stream));
 }
 
 fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const void *k_cache,

@@ -183,6 +183,8 @@ template <bool PAGED> struct KvRows {
             pages = min(max(entry, 0), p.n_pages - 1);
         }
     }
+    // row of chunk-relative key `key` from the start of the buffer or pool (for the store of an appended row)
+    __device__ __forceinline__ size_t absolute(int key) const { return base + (*this)(key); }
     // row of chunk-relative key `key`, relative to `base`
     __device__ __forceinline__ size_t operator()(int key) const
     {
@@ -247,6 +249,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     // A fused append puts the new key at offset jn of exactly one chunk of the row.
     const int jn = S_res - start;
     const bool owner = (S != S_res) & (jn >= 0) & (jn < C);
+    // where the appended row goes (all lanes take part in the page lookup of a paged cache)
+    const size_t row_new = at.absolute(owner ? jn : 0);
     // With early loads an empty chunk takes the ordinary path below (no block beyond the
     // first is touched, every key is masked): a branch here would pull the loads behind it.
     if (!EARLY && nvalid <= 0) {               // empty chunk: zero partials, no flag
@@ -351,9 +355,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
             den += e;
             axpy8(acc, e, vn);
             if (hq == hkv * p.G) {                  // one writer per KV head
-                const size_t at = (((size_t)b * p.Hkv + hkv) * p.Smax + S_res) * kHeadDim;
-                reinterpret_cast<u32x4 *>(p.k_store + at)[seg] = kn;
-                reinterpret_cast<u32x4 *>(p.v_store + at)[seg] = vn;
+                reinterpret_cast<u32x4 *>(p.k_store)[row_new + seg] = kn;
+                reinterpret_cast<u32x4 *>(p.v_store)[row_new + seg] = vn;
             }
         }
         const unsigned long long any_bad = __ballot(bad);
@@ -413,9 +416,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         if (owner && hq == hkv * p.G && wave == 0 && sub == 0 && p.k_store) {
             // a recomputed chunk of the fused kernels has stored the rows already; the
             // synchronized entry points come here first
-            const size_t at = (((size_t)b * p.Hkv + hkv) * p.Smax + S_res) * kHeadDim;
-            reinterpret_cast<u32x4 *>(p.k_store + at)[seg] = *knp;
-            reinterpret_cast<u32x4 *>(p.v_store + at)[seg] = vn;
+            reinterpret_cast<u32x4 *>(p.k_store)[row_new + seg] = *knp;
+            reinterpret_cast<u32x4 *>(p.v_store)[row_new + seg] = vn;
         }
     }
 

@@ -204,6 +204,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     // the reduction below, multiplied with the step's V row.
     float e_new = 0.f;
     int f_new = 0;
+    const size_t row_new = at.absolute(owner ? S_res - start : 0);   // where the appended row goes (all lanes look the page up)
     if (owner) {
         const int hh = 4 * wave + g;
         const size_t at_new = (size_t)gi * kHeadDim;
@@ -215,9 +216,8 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
             e_new = __builtin_amdgcn_exp2f(d * kLog2e);
         }
         if (wave == 0 && g == 0) {             // 16 lanes put the rows into the cache
-            const size_t at = ((size_t)gi * p.Smax + S_res) * kHeadDim;
-            reinterpret_cast<u32x4 *>(p.k_store + at)[n] = kn;
-            reinterpret_cast<u32x4 *>(p.v_store + at)[n] = reinterpret_cast<const u32x4 *>(p.v_new + at_new)[n];
+            reinterpret_cast<u32x4 *>(p.k_store)[row_new + n] = kn;
+            reinterpret_cast<u32x4 *>(p.v_store)[row_new + n] = reinterpret_cast<const u32x4 *>(p.v_new + at_new)[n];
         }
     }
 

@@ -86,6 +86,9 @@ _lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _
 
 _lib.fd_decode_attn_paged.restype = ctypes.c_int
 _lib.fd_decode_attn_paged.argtypes = [_sp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp, Workspace, _vp]
+_lib.fd_decode_attn_paged_append.restype = ctypes.c_int
+_lib.fd_decode_attn_paged_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp,
+                                            Workspace, _vp]
 _lib.fd_decode_attn_append.restype = ctypes.c_int
 _lib.fd_decode_attn_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
 
@@ -96,7 +99,7 @@ _lib.fd_prefill_attn.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Works
 _lib.fd_prefill_get_flags.restype = ctypes.c_int
 _lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
 
-EXPORTS = ("fd_decode_attn_paged", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+EXPORTS = ("fd_decode_attn_paged", "fd_decode_attn_paged_append", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
            "fd_status_str")
@@ -206,6 +209,12 @@ def fd_decode_attn_paged(shape, q, k_pool, v_pool, block_table, page_size, n_pag
                          ws_ptr, ws_bytes, stream=0):
     _check(_lib.fd_decode_attn_paged(ctypes.byref(shape), q, k_pool, v_pool, block_table, page_size, n_pages, seq_lens, phi,
                                      Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_paged_append(shape, q, k_new, v_new, k_pool, v_pool, block_table, page_size, n_pages, seq_lens, phi, bounds,
+                                out, ws_ptr, ws_bytes, stream=0):
+    _check(_lib.fd_decode_attn_paged_append(ctypes.byref(shape), q, k_new, v_new, k_pool, v_pool, block_table, page_size, n_pages,
+                                            seq_lens, phi, Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
 
 
 def fd_prefill_workspace_bytes(shape):

@@ -102,6 +102,56 @@ def test_paged_flag_and_recompute(H, Hq, Hkv):
     assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,Smax,lens,page,chunk", [
+    (4, 4, 4, 512, [300, 256, 511, 512], 64, 256),     # mid-page; first row of a fresh page; last free row; full (dropped)
+    (3, 8, 8, 1024, [0, 1, 1023], 16, 128),            # empty sequence: the new key is the only one
+    (2, 32, 32, 2048, [2047, 1000], 256, 1024),        # 8-wavefront workgroups
+    (2, 16, 2, 1024, [1000, 512], 32, 256),            # grouped kernel; a fresh page that opens a chunk
+    (8, 32, 32, 2048, None, 128, 256),                 # every sequence full: nothing appended, second launch
+])
+def test_paged_append(H, B, Hq, Hkv, Smax, lens, page, chunk):
+    case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=8300 + page + chunk, seq_lens=lens, poison_padding=True)
+    rng = np.random.default_rng(8301)
+    k_new = rng.standard_normal((B, Hkv, 128)).astype(np.float16)
+    v_new = rng.standard_normal((B, Hkv, 128)).astype(np.float16)
+    sl = np.clip(np.asarray(case["seq_lens"], dtype=np.int64), 0, Smax)
+    # the cache after the step (host side): rows in place, lengths that include the new token
+    after = dict(case)
+    after["k"], after["v"] = case["k"].copy(), case["v"].copy()
+    for b in range(B):
+        if sl[b] < Smax:
+            after["k"][b, :, sl[b]] = k_new[b]
+            after["v"][b, :, sl[b]] = v_new[b]
+    sl2 = np.minimum(sl + 1, Smax).astype(np.int32)
+    after["seq_lens"] = sl2
+    pc = PagedCase(H, after, page, chunk)                # pools and table of the state after the step
+    want = po.attn_exact(case["q"], pc.k_pool, pc.v_pool, pc.table, page, sl2, case["scale"], nthreads=8)
+    ocf, orf, margin = po.flags(case["q"], pc.k_pool, pc.table, page, sl2, case["scale"], synth.PHI, LO, HI, chunk, nthreads=8)
+    assert margin.min() > 1e-2
+    # the state before the step: the rows that will be written hold poison
+    for b in range(B):
+        if sl[b] < Smax:
+            pid, r = pc.table[b, sl[b] // page], sl[b] % page
+            pc.kp[pid, :, r] = float("nan")
+            pc.vp[pid, :, r] = float("nan")
+    dc = pc.dc
+    dc.seq_lens.copy_(torch.from_numpy(sl.astype(np.int32)))
+    kn, vn = torch.from_numpy(k_new).to(dc.dev), torch.from_numpy(v_new).to(dc.dev)
+    dc.out.fill_(float("nan"))
+    dc.last_entry = "fd_decode_attn_paged_append"
+    fdattn.fd_decode_attn_paged_append(dc.shape, dc.q.data_ptr(), kn.data_ptr(), vn.data_ptr(), pc.kp.data_ptr(), pc.vp.data_ptr(),
+                                       pc.tb.data_ptr(), page, pc.k_pool.shape[0], dc.seq_lens.data_ptr(), synth.PHI,
+                                       synth.BOUNDS, dc.out.data_ptr(), *dc._ws(), dc._stream())
+    torch.cuda.synchronize()
+    H.assert_close(dc.out.cpu().numpy().astype(np.float64), want, "paged append, page %d chunk %d" % (page, chunk))
+    # the pools: bit for bit the state after the step, nothing else touched (poison stays poison)
+    assert np.array_equal(pc.kp.cpu().numpy().view(np.uint16), pc.k_pool.view(np.uint16))
+    assert np.array_equal(pc.vp.cpu().numpy().view(np.uint16), pc.v_pool.view(np.uint16))
+    dc.seq_lens.copy_(torch.from_numpy(sl2))
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+
+
 def test_paged_rejects_bad_arguments():
     dev = torch.device("cuda:0")
     buf = torch.zeros(1 << 22, dtype=torch.uint8, device=dev)

@@ -183,6 +183,18 @@ template <bool PAGED> struct KvRows {
             pages = min(max(entry, 0), p.n_pages - 1);
         }
     }
+    // First row, relative to `base`, of the 16 keys key0 .. key0 + 15 (key0 a multiple of 16, the same
+    // for the whole wavefront): they share a page, which one lane-to-scalar read finds.
+    __device__ __forceinline__ size_t block16(int key0) const
+    {
+        if constexpr (PAGED) {
+            const int t = start + key0;
+            const int page = __builtin_amdgcn_readlane(pages, (t >> shift) - first);
+            return ((((size_t)page * Hkv + hkv) << shift) + (size_t)(t & ((1 << shift) - 1))) * 16;
+        } else {
+            return (size_t)key0 * 16;
+        }
+    }
     // row of chunk-relative key `key` from the start of the buffer or pool (for the store of an appended row)
     __device__ __forceinline__ size_t absolute(int key) const { return base + (*this)(key); }
     // row of chunk-relative key `key`, relative to `base`

@@ -123,6 +123,15 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     // Keys past the valid length re-read the last valid key and get weight zero.
     auto issue = [&](int blk, u32x4 (&kk)[4], u32x4 (&vv)[4]) {
         const int k0 = blk * 16;
+        if constexpr (PAGED) {
+            // the block holds a resident key (k0 <= last), so a clamped key stays inside it: one page per block
+            const size_t row0 = at.block16(k0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + row0 + (size_t)(min(k0 + 4 * i + g, last) - k0) * 16);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + row0 + (size_t)(min(k0 + 4 * r + g, last) - k0) * 16);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + at(min(k0 + 4 * i + g, last)));
 #pragma unroll

@@ -87,3 +87,55 @@ def test_prefill_pins_reject_a_planted_mistake(tmp_path, what, old, new):
     r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_prefill.py"), "-x", "-q",
                         "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
     assert r.returncode != 0, "the pins accept a prefill oracle with this mistake: %s" % what
+
+
+# ---- the paged-cache oracle (Python): the same exercise, in process ----
+PAGED_SRC = os.path.join(ROOT, "oracle", "fd_paged_oracle.py")
+PAGED_MUTANTS = [
+    ("pages put back in reverse order", "pid = int(table[b, j])", "pid = int(table[b, (n + P - 1) // P - 1 - j])"),
+    ("the partly filled last page dropped", "for j in range((n + P - 1) // P):", "for j in range(n // P):"),
+    ("the table read transposed", "pid = int(table[b, j])", "pid = int(table.reshape(-1)[j * B + b])"),
+    ("KV heads of a page reversed", "= pool[pid]", "= pool[pid][::-1]"),
+    ("rows of a page shifted by one", "= pool[pid]", "= np.roll(pool[pid], 1, axis=1)"),
+    ("V gathered from the K pool", "v = gather_pages(v_pool, table, page_size, seq_lens)", "v = gather_pages(k_pool, table, page_size, seq_lens)"),
+    ("lengths not clamped to the table's capacity", "n = int(min(max(int(seq_lens[b]), 0), T * P))", "n = int(seq_lens[b])"),
+]
+
+
+def _paged_pin_calls(pins):
+    calls = [(pins.test_gather_follows_the_table_token_by_token, (P,)) for P in (4, 16, 32)]
+    calls += [(pins.test_identity_table_is_the_contiguous_cache, ())]
+    calls += [(pins.test_paged_attention_equals_contiguous_attention, (P,)) for P in (8, 32)]
+    calls += [(pins.test_placement_in_the_pool_and_unused_pages_do_not_matter, ()), (pins.test_brute_force_one_row, ()),
+              (pins.test_flags_count_logical_positions, ()), (pins.test_lengths_beyond_the_capacity_are_clamped, ())]
+    return calls
+
+
+def _load_paged(text):
+    import types
+    mod = types.ModuleType("oracle.fd_paged_oracle_variant")
+    mod.__package__ = "oracle"
+    exec(compile(text, PAGED_SRC, "exec"), mod.__dict__)
+    return mod
+
+
+@pytest.mark.parametrize("what,old,new", PAGED_MUTANTS, ids=[m[0] for m in PAGED_MUTANTS])
+def test_paged_pins_reject_a_planted_mistake(monkeypatch, what, old, new):
+    import test_oracle_paged as pins
+    text = open(PAGED_SRC).read()
+    assert text.count(old) >= 1, "the paged oracle no longer contains the line this case mutates: %r" % old
+    monkeypatch.setattr(pins, "po", _load_paged(text.replace(old, new)))
+    failed = 0
+    for fn, a in _paged_pin_calls(pins):
+        try:
+            fn(*a)
+        except Exception:
+            failed += 1
+    assert failed, "the pins accept a paged oracle with this mistake: %s" % what
+
+
+def test_paged_pins_accept_the_unmutated_copy(monkeypatch):
+    import test_oracle_paged as pins
+    monkeypatch.setattr(pins, "po", _load_paged(open(PAGED_SRC).read()))
+    for fn, a in _paged_pin_calls(pins):
+        fn(*a)

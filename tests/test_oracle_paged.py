@@ -91,3 +91,15 @@ def test_flags_count_logical_positions():
     want = fd_oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], 3.0, -60.0, 20.0, 64)
     assert np.array_equal(cf, want[0]) and np.array_equal(rf, want[1])
     assert cf[0, 1].tolist() == [0, 1] and cf[0, 0].sum() == 0      # token 70 sits in chunk 1, whatever page holds it
+
+
+def test_lengths_beyond_the_capacity_are_clamped():
+    # seq_lens above the table's capacity (and below zero) are clamped, as everywhere in the library
+    case = small_case(16, B=2, Hq=2, Hkv=2, Smax=64, lens=(64, 64))
+    P = 16
+    k_pool, v_pool, table = synth.to_pages(case, P, seed=9)
+    want = po.attn_exact(case["q"], k_pool, v_pool, table, P, np.array([64, 64]), case["scale"])
+    got = po.attn_exact(case["q"], k_pool, v_pool, table, P, np.array([1000, 64]), case["scale"])
+    assert np.array_equal(got, want)
+    neg = po.attn_exact(case["q"], k_pool, v_pool, table, P, np.array([-5, 64]), case["scale"])
+    assert not neg[0].any() and np.array_equal(neg[1], want[1])

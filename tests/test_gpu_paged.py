@@ -152,6 +152,34 @@ def test_paged_append(H, B, Hq, Hkv, Smax, lens, page, chunk):
     assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
 
 
+def test_paged_long_context_and_graph_replay(H):
+    # 128K tokens in 8192 pages of 16 (64 pages per chunk, 128 chunks per row), then the same call
+    # recorded by a stream capture and replayed with eager calls in between
+    case = synth.make_case(B=1, Hq=8, Hkv=8, D=128, Smax=131072, seq_lens=[131072 - 777], seed=8400)
+    pc = PagedCase(H, case, 16, 1024)
+    want = po.attn_exact(case["q"], pc.k_pool, pc.v_pool, pc.table, 16, case["seq_lens"], case["scale"], nthreads=8)
+    eager = pc.run()
+    H.assert_close(eager, want, "paged, 128K context")
+    dc = pc.dc
+    side = torch.cuda.Stream(device=dc.dev)
+    graph = torch.cuda.CUDAGraph()
+    out_g = torch.full_like(dc.out, float("nan"))
+    side.wait_stream(torch.cuda.current_stream(dc.dev))
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fdattn.fd_decode_attn_paged(dc.shape, dc.q.data_ptr(), pc.kp.data_ptr(), pc.vp.data_ptr(), pc.tb.data_ptr(), 16,
+                                        pc.k_pool.shape[0], dc.seq_lens.data_ptr(), synth.PHI, synth.BOUNDS,
+                                        out_g.data_ptr(), *dc._ws(), side.cuda_stream)
+    torch.cuda.synchronize(dc.dev)
+    for i in range(3):
+        out_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize(dc.dev)
+        assert np.array_equal(out_g.cpu().numpy().astype(np.float64), eager), "replay %d differs from the eager call" % i
+        assert np.array_equal(pc.run(), eager)
+    del graph
+
+
 def test_paged_rejects_bad_arguments():
     dev = torch.device("cuda:0")
     buf = torch.zeros(1 << 22, dtype=torch.uint8, device=dev)

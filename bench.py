@@ -334,6 +334,31 @@ def main():
         extras["logit_histogram"] = {"us": round(t_stats * 1e6, 2), "k_bytes": kv_bytes // 2,
                                      "k_gbs": round(kv_bytes / 2 / t_stats / 1e9, 1),
                                      "note": "K read once per query head; with grouped heads the repeats hit in L2"}
+        # the same rotation of calls recorded once by a stream capture and replayed as a graph
+        # (what a serving loop would do; the calls are capturable: launches only, no allocation)
+        try:
+            side = torch.cuda.Stream(device=dev)
+            graph = torch.cuda.CUDAGraph()
+            side.wait_stream(torch.cuda.current_stream(dev))
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(graph, stream=side):
+                    for l in range(layers):
+                        a = (run.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr())
+                        getattr(fdattn, entry)(*a, phi, bounds, out.data_ptr(), run.ws.data_ptr(), run.ws_bytes, side.cuda_stream)
+            torch.cuda.synchronize()
+            reps = max(2, short // layers)
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                graph.replay()
+            torch.cuda.synchronize()
+            extras["graph_replay_us"] = round((time.perf_counter() - t0) / (reps * layers) * 1e6, 2)
+            del graph
+        except RuntimeError as e:                       # capture not available: report, do not fail the run
+            extras["graph_replay_us"] = None
+            extras["graph_replay_error"] = str(e)[:200]
         # cache-resident figure: the same KV set every call (fits the last-level cache at c0 and c1)
         extras["hot_cache_us"] = round(wall(lambda i: run.step(0), short, 10) * 1e6, 2)
         if planted:

@@ -159,6 +159,41 @@ def test_lower_bound_flags_too(H):
     H.assert_close(got.reshape(-1, 128), want, "prefill, all tiles recomputed")
 
 
+def test_prefill_can_be_captured_and_replayed(H):
+    # two launches on the caller's stream and nothing else: a stream capture of the call replays,
+    # also when a tile is flagged and recomputed inside the kernel
+    B, Hq, Hkv, Smax = 1, 4, 2, 512
+    q, k, v, sl = draw(B, Hq, Hkv, Smax, [500], seed=7500)
+    scale = float(np.float32(1.0 / np.sqrt(128.0)))
+    q[0, 1, 300:500, 7] = np.float16(12.0)
+    k[0, 0, 300] = 0
+    k[0, 0, 300, 7] = np.float16(36.0)                 # head 1 overflows from token 300 on
+    eager, tf = run_gpu(q, k, v, sl, scale)
+    assert tf[0, 1].sum() > 0 and tf[0, 0].sum() == 0
+    dev = torch.device("cuda:0")
+    tq, tk, tv = (torch.from_numpy(a).to(dev) for a in (q, k, v))
+    tsl = torch.from_numpy(sl).to(dev)
+    out = torch.full((B, Hq, Smax, 128), float("nan"), dtype=torch.float16, device=dev)
+    shape = fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, scale)
+    nws = fdattn.fd_prefill_workspace_bytes(shape)
+    ws = torch.full((nws,), 0x5A, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream(device=dev)
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream(dev))
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fdattn.fd_prefill_attn(shape, tq.data_ptr(), tk.data_ptr(), tv.data_ptr(), tsl.data_ptr(), synth.PHI, synth.BOUNDS,
+                                   out.data_ptr(), ws.data_ptr(), nws, side.cuda_stream)
+    torch.cuda.synchronize()
+    for i in range(3):
+        out.fill_(float("nan"))
+        ws.fill_(0x11 * (i + 1))                        # the workspace needs no particular contents
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), eager), "replay %d differs from the eager call" % i
+    del graph
+
+
 def test_prefill_rejects_bad_arguments():
     dev = torch.device("cuda:0")
     buf = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)

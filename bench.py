@@ -313,7 +313,7 @@ def main():
     if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # chunk sweep (us per layer-step of the whole call)
         sweep = {}
-        for c in (256, 512, 1024):
+        for c in sorted({256, 512, 1024, chunk}):
             r = run if c == chunk else Runner(c, entry)
             sweep[str(c)] = round(wall(r.step, short, 10) * 1e6, 2)
         extras["chunk_sweep_us"] = sweep

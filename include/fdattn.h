@@ -35,7 +35,7 @@
  *   (null pointer, unsupported shape, bad bounds, workspace too small) are
  *   reported before anything is enqueued.  A failed launch returns FD_ERR_HIP.
  * Threads.  Calls are re-entrant as long as they use distinct workspaces.
- * Supported shapes.  head_dim == 128; chunk in {64, 128, 256, 512, 1024};
+ * Supported shapes.  head_dim == 128; chunk in {64, 128, 256, 512, 1024, 2048, 4096};
  *   n_q_heads a multiple of n_kv_heads; batch*n_q_heads*ceil(max_seq/chunk)
  *   < 2^31.
  */
@@ -86,7 +86,7 @@ typedef struct { void *ptr; size_t bytes; } fd_workspace;
 size_t fd_workspace_bytes(const fd_shape *shape);
 
 /* A chunk size (keys per partial vector, Section 3's split of the sequence axis)
- * suited to this shape on MI355X, one of 64, 128, 256, 512, 1024; shape->chunk is
+ * suited to this shape on MI355X, one of 64 ... 1024 (up to 4096 for grouped heads); shape->chunk is
  * ignored.  0 if the rest of the shape is invalid or unsupported.  The paper leaves
  * the split size open; any supported value gives the same result up to rounding.
  * Pure host function.                                                          */

@@ -27,7 +27,7 @@ fd_status plan(const fd_shape *sh, Layout *L)
     if (!std::isfinite(sh->scale)) return FD_ERR_SHAPE;
     if (sh->head_dim != fd::kHeadDim) return FD_ERR_UNSUPPORTED;
     switch (sh->chunk) {
-        case 64: case 128: case 256: case 512: case 1024: break;
+        case 64: case 128: case 256: case 512: case 1024: case 2048: case 4096: break;
         default: return FD_ERR_UNSUPPORTED;
     }
     const long long rows = (long long)sh->batch * sh->n_q_heads;
@@ -157,13 +157,17 @@ size_t fd_workspace_bytes(const fd_shape *shape)
     return plan(shape, &L) == FD_OK ? L.total : 0;
 }
 
-// Chunk size from the shape alone (shape->chunk is ignored).  Fitted to sweeps over
-// 64..1024 keys on MI355X: one workgroup streams one chunk, so a chunk should be as
-// long as possible (fewer partial results, fewer hand-overs) while the launch still
-// covers the 256 CUs -- and, when sequences of a batch may differ in length, while
-// there are enough workgroups per CU (about 16) to even out ragged rows.  The
-// grouped kernel has 1/G as many workgroups and a heavier per-workgroup tail; it
-// wants the longest chunk that still gives every CU four of them.
+// Chunk size from the shape alone (shape->chunk is ignored).  Fitted to sweeps on MI355X:
+// one workgroup streams one chunk, so a chunk should be as long as possible (fewer partial
+// results, fewer hand-overs) while the launch still covers the 256 CUs.
+//   per-row kernel: chunks beyond 1024 keys lose (fewer, longer workgroups hide less latency);
+//     when sequences of a batch may differ in length it wants enough workgroups per CU (about
+//     16) to even out ragged rows.
+//   grouped kernel: 1/G as many workgroups, each with four wavefronts' worth of loads in flight
+//     and a heavy tail (reduction over the group's heads); it is fastest with one workgroup
+//     per CU -- a single launch that finishes its rows itself -- so: the longest chunk, up to
+//     4096 keys, that still gives 256 workgroups (B x 64/8 heads x 4096 keys: 26.5 us at 1024 keys
+//     against 31.0 at 256 for B = 8; 84.5 at 4096 against 89.8 at 1024 for B = 32).
 int32_t fd_pick_chunk(const fd_shape *shape)
 {
     if (!shape) return 0;
@@ -171,24 +175,24 @@ int32_t fd_pick_chunk(const fd_shape *shape)
     sh.chunk = 64;
     Layout L;
     if (plan(&sh, &L) != FD_OK) return 0;
-    static const int32_t sizes[] = {1024, 512, 256, 128, 64};
+    static const int32_t sizes[] = {4096, 2048, 1024, 512, 256, 128, 64};
     const bool grouped = sh.n_q_heads != sh.n_kv_heads;
     const long long units = (long long)sh.batch * (grouped ? sh.n_kv_heads : sh.n_q_heads);
     auto workgroups = [&](int32_t c) { return units * (((long long)sh.max_seq + c - 1) / c); };
-    auto largest_with = [&](long long want) -> int32_t {
+    auto largest_with = [&](long long want, int32_t longest) -> int32_t {
         for (int32_t c : sizes)
-            if (workgroups(c) >= want) return c;
+            if (c <= longest && workgroups(c) >= want) return c;
         return 0;
     };
     int32_t c = 0;
     if (grouped) {
-        c = largest_with(1024);
+        c = largest_with(256, 4096);
     } else if (workgroups(1024) >= 4096) {
         c = 1024;
     } else if (sh.batch > 1) {
-        c = largest_with(4096);
+        c = largest_with(4096, 1024);
     }
-    if (!c) c = largest_with(256);
+    if (!c) c = largest_with(256, grouped ? 4096 : 1024);
     return c ? c : 64;
 }
 

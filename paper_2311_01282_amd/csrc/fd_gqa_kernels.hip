@@ -333,6 +333,8 @@ hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s)
         case 256:  return GqaLauncher<256>::run(p, s);
         case 512:  return GqaLauncher<512>::run(p, s);
         case 1024: return GqaLauncher<1024>::run(p, s);
+        case 2048: return GqaLauncher<2048>::run(p, s);
+        case 4096: return GqaLauncher<4096>::run(p, s);
         default:   return hipErrorInvalidValue;
     }
 }

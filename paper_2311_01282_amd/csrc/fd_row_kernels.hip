@@ -107,6 +107,8 @@ hipError_t dispatch_chunk(int C, Args... args)
         case 256:  return Launcher<256>::run(args...);
         case 512:  return Launcher<512>::run(args...);
         case 1024: return Launcher<1024>::run(args...);
+        case 2048: return Launcher<2048>::run(args...);
+        case 4096: return Launcher<4096>::run(args...);
         default:   return hipErrorInvalidValue;
     }
 }

@@ -136,7 +136,8 @@ def test_pick_chunk_is_a_supported_size_and_ignores_the_chunk_field(fdattn):
             picks.add(fdattn.fd_pick_chunk(sh))
         assert len(picks) == 1, name
         c = picks.pop()
-        assert c in (64, 128, 256, 512, 1024), name
+        assert c in (64, 128, 256, 512, 1024, 2048, 4096), name
+        assert c <= 1024 or cfg["Hq"] != cfg["Hkv"], name          # long chunks are for grouped heads only
         # the picked size is accepted by the sizing call
         assert fdattn.fd_workspace_bytes(fdattn.make_shape(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"], c, 0.1)) > 0
 
@@ -144,11 +145,14 @@ def test_pick_chunk_is_a_supported_size_and_ignores_the_chunk_field(fdattn):
 def test_pick_chunk_fills_the_chip_when_the_shape_allows_it(fdattn):
     # one workgroup per (row or head group, chunk): at least 256 of them when any supported size gives that many
     for (B, Hq, Hkv, Smax) in [(1, 32, 32, 1024), (1, 32, 32, 8192), (16, 32, 32, 4096), (32, 64, 8, 4096),
-                               (4, 32, 32, 32768), (1, 8, 8, 300), (1, 1, 1, 64), (3, 40, 40, 5000)]:
+                               (4, 32, 32, 32768), (1, 8, 8, 300), (1, 1, 1, 64), (3, 40, 40, 5000), (8, 64, 8, 4096),
+                               (64, 64, 8, 4096), (1, 64, 8, 32768), (2, 32, 8, 8192)]:
         c = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, 0.1))
         units = B * (Hkv if Hq != Hkv else Hq)
         wgs = lambda cc: units * (-(-Smax // cc))
-        assert c in (64, 128, 256, 512, 1024)
+        assert c in (64, 128, 256, 512, 1024, 2048, 4096)
+        if Hq != Hkv and wgs(c) >= 256 and c < 4096:
+            assert wgs(2 * c) < 256, (B, Hq, Hkv, Smax, c)        # grouped: the longest chunk that still fills the chip
         if wgs(64) >= 256:
             assert wgs(c) >= 256, (B, Hq, Hkv, Smax, c)
         else:

@@ -26,6 +26,8 @@ CASES = [
     (2, 6, 3, 1500, [1500, 17], 512),       # group of 2, a 17-key sequence
     (1, 16, 1, 2100, [2050], 1024),         # group of 16 (the tile is full), one short last chunk
     (3, 12, 4, 700, [0, 700, 1], 128),      # group of 3 (not a power of two), an empty sequence
+    (2, 16, 2, 5000, [5000, 2049], 2048),   # long chunks: a ragged last one, one key in a chunk
+    (2, 16, 2, 9000, [8999, 4097], 4096),   # the longest chunk
 ]
 
 
@@ -65,17 +67,18 @@ def test_gqa_partial_sums_match_eq4(oracle, H):
     np.testing.assert_allclose(num, onum, rtol=0, atol=2e-5 * np.abs(oden).max())
 
 
-def test_gqa_flags_are_per_query_head_and_rows_recomputed(oracle, H):
-    case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=2048, seed=420, seq_lens=[2048, 1111],
+@pytest.mark.parametrize("Smax,lens,chunk", [(2048, [2048, 1111], 256), (8192, [8192, 5000], 4096)])
+def test_gqa_flags_are_per_query_head_and_rows_recomputed(oracle, H, Smax, lens, chunk):
+    case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=Smax, seed=420, seq_lens=lens,
                            poison_padding=True)
     planted = synth.plant_keys(case, 3, 36.0, seed=421, allow_shared_kv=True)
     want = exact(oracle, case)
-    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, 256)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk)
     assert margin.min() > 1e-2
     for b, h, _ in planted:
         assert orf[b, h]
     assert orf.sum() < orf.size                     # other heads of the groups stay unflagged
-    dc = H.DeviceCase(case, chunk=256)
+    dc = H.DeviceCase(case, chunk=chunk)
     for _ in range(2):                              # twice: the arrival counters must reset
         got = dc.run("fd_decode_attn_gqa")
         H.assert_close(got, want, "gqa + recompute")

@@ -78,6 +78,8 @@ def check(H, case, page, chunk, expect_flagged=0):
     (2, 16, 2, 1024, [1023, 256], 16, 256),            # grouped kernel, groups of 8
     (2, 12, 4, 512, [512, 0], 64, 128),                # groups of 3; empty sequence
     (1, 64, 8, 4096, [4000], 256, 1024),               # grouped, long chunks
+    (2, 16, 2, 8192, [8191, 4097], 64, 4096),          # the longest chunk over its 64 pages
+    (2, 4, 4, 4096, [4096, 2049], 256, 2048),          # per-row kernel, 2048-key chunks
 ])
 def test_paged_matches_oracle_and_contiguous(H, B, Hq, Hkv, Smax, lens, page, chunk):
     case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=8100 + page + chunk, seq_lens=lens,

@@ -29,6 +29,8 @@ SMALL = [
     (2, 2, 2, 2048, [2048, 1025], 1024),              # largest chunk, one key in the last
     (2, 2, 2, 1536, [0, 1300], 512),                  # an empty sequence
     (1, 8, 2, 700, [700], 128),                       # grouped heads through the per-row path
+    (2, 4, 4, 5000, [5000, 2049], 2048),              # long chunks: a ragged last one, one key in a chunk
+    (2, 4, 4, 9000, [8999, 4097], 4096),              # the longest chunk
 ]
 
 

@@ -166,8 +166,9 @@ size_t fd_workspace_bytes(const fd_shape *shape)
 //   grouped kernel: 1/G as many workgroups, each with four wavefronts' worth of loads in flight
 //     and a heavy tail (reduction over the group's heads); it is fastest with one workgroup
 //     per CU -- a single launch that finishes its rows itself -- so: the longest chunk, up to
-//     4096 keys, that still gives 256 workgroups (B x 64/8 heads x 4096 keys: 26.5 us at 1024 keys
-//     against 31.0 at 256 for B = 8; 84.5 at 4096 against 89.8 at 1024 for B = 32).
+//     4096 keys, that still gives 256 workgroups and fills its last round of the chip
+//     (B x 64/8 heads x 4096 keys: 26.5 us at 1024 keys against 31.0 at 256 for B = 8; 84.5 at
+//     4096 against 89.8 at 1024 for B = 32).
 int32_t fd_pick_chunk(const fd_shape *shape)
 {
     if (!shape) return 0;
@@ -186,7 +187,16 @@ int32_t fd_pick_chunk(const fd_shape *shape)
     };
     int32_t c = 0;
     if (grouped) {
-        c = largest_with(256, 4096);
+        // the longest chunk whose workgroups fill whole rounds of the 256 CUs to 90 % (384 workgroups
+        // would leave half the chip idle in their second round: 139 us against 128 us with 768)
+        double best = 0.0;
+        for (int32_t cand : sizes) {
+            const long long w = workgroups(cand);
+            if (w < 256) continue;
+            const double fill = (double)w / (256.0 * (double)((w + 255) / 256));
+            if (fill >= 0.9) { c = cand; break; }
+            if (fill > best) { best = fill; c = cand; }
+        }
     } else if (workgroups(1024) >= 4096) {
         c = 1024;
     } else if (sh.batch > 1) {

@@ -249,6 +249,23 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     if (lane == 0) lds.bad[wave] = bad_mask;
     if (n == 0) { lds.e_new[4 * wave + g] = e_new; lds.f_new[4 * wave + g] = f_new; }
     __syncthreads();
+    const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
+    // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
+    unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
+#pragma unroll
+    for (int h = 0; h < 16; ++h) flagged_heads |= (unsigned)(lds.f_new[h] != 0) << h;
+    auto den_of = [&](int h) {                 // Eq. 4's denominator of head h over this chunk
+        float s = lds.e_new[h];
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) s += lds.den[w][h + 16 * q4];
+        return s;
+    };
+    // A sequence of one chunk whose guard stayed quiet is complete here: its rows' results are
+    // this workgroup's own sums, so they go out directly instead of through the workspace and
+    // the epilogue (same arithmetic: the epilogue's factors are exactly 1 for such a row).
+    const bool solo = p.elect && nb == 1 && !flagged_heads;
     // 4 consecutive elements per thread: one 16-byte LDS read per wavefront tile, 16 bytes out
     for (int i = 4 * tid; i < G * kHeadDim; i += 4 * kGqaThreads) {
         const float4 a = *reinterpret_cast<const float4 *>(&lds.tile[i]);
@@ -265,31 +282,31 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
             o.x = __builtin_fmaf(en, (float)v01.x, o.x); o.y = __builtin_fmaf(en, (float)v01.y, o.y);
             o.z = __builtin_fmaf(en, (float)v23.x, o.z); o.w = __builtin_fmaf(en, (float)v23.y, o.w);
         }
+        if (solo) {
+            const float l = den_of(i / kHeadDim);
+            uint2 h;
+            h.x = (unsigned)to_half_bits(o.x / l) | ((unsigned)to_half_bits(o.y / l) << 16);
+            h.y = (unsigned)to_half_bits(o.z / l) | ((unsigned)to_half_bits(o.w / l) << 16);
+            *reinterpret_cast<uint2 *>(p.out + (size_t)(row0 + i / kHeadDim) * kHeadDim + d0) = h;
+        }
         float *dst = &p.ws.num[((size_t)(row0 + i / kHeadDim) * p.nc + c) * kHeadDim + d0];
-        if (p.elect) {      // read by another workgroup of this launch: write through
+        if (p.elect && !solo) {      // read by another workgroup of this launch: write through
             store_coherent4(dst, o.x, o.y, o.z, o.w);
         } else {
             *reinterpret_cast<float4 *>(dst) = o;
         }
     }
-    const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
-    // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
-    unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
-#pragma unroll
-    for (int h = 0; h < 16; ++h) flagged_heads |= (unsigned)(lds.f_new[h] != 0) << h;
     if (tid < G) {
-        float s = lds.e_new[tid];
-#pragma unroll
-        for (int w = 0; w < 4; ++w)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) s += lds.den[w][tid + 16 * q4];
+        const float s = den_of(tid);
         const size_t slot = (size_t)(row0 + tid) * p.nc + c;
         const int f = (flagged_heads >> tid) & 1;
         store_coherent(&p.ws.den[slot], s);
         store_coherent(&p.ws.mloc[slot], p.phi);
         store_meta(p, slot, s, p.phi, f);
         p.ws.chunk_flags[slot] = (uint8_t)f;
+        if (solo) p.ws.row_flags[row0 + tid] = 0;
     }
+    if (solo) return;
 
     // Section 3 "Recomputation": a (head, chunk) whose guard fired is redone with the
     // synchronized scheme on the per-row path (rare; re-reads this chunk only).

@@ -80,6 +80,8 @@ def check(oracle, H, case, chunk, k_new=None, v_new=None, seed=1, expect_flagged
     (1, 64, 8, 4096, [4000], 1024),                   # grouped, long chunks
     (16, 64, 8, 1024, None, 256),                     # grouped, 512 workgroups: second launch
     (1, 34, 2, 300, [299], 64),                       # groups of 17: per-row kernel with shared KV heads
+    (3, 16, 2, 512, [300, 510, 0], 512),              # grouped, one chunk per sequence: no epilogue; new key alone
+    (2, 16, 2, 1024, [512, 511], 512),                # grouped: the new key opens a second chunk / completes the only one
 ])
 def test_append_matches_concatenate_then_attend(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
     if lens is None:
@@ -91,7 +93,7 @@ def test_append_matches_concatenate_then_attend(oracle, H, B, Hq, Hkv, Smax, len
 def test_append_of_an_overflowing_key_is_flagged_and_recomputed(oracle, H):
     # the new key itself leaves the bounds (logit ~ +36): its chunk is redone with the
     # synchronized scheme, new key included; per-row and grouped kernels
-    for (Hq, Hkv, lens, chunk) in ((4, 4, [700, 512], 256), (16, 2, [700, 512], 256)):
+    for (Hq, Hkv, lens, chunk) in ((4, 4, [700, 512], 256), (16, 2, [700, 512], 256), (16, 2, [700, 512], 1024)):
         case = synth.make_case(B=2, Hq=Hq, Hkv=Hkv, D=128, Smax=1024, seq_lens=lens, seed=91, poison_padding=True)
         G = Hq // Hkv
         k_new = np.random.default_rng(3).standard_normal((2, Hkv, 128)).astype(np.float16)

@@ -28,6 +28,9 @@ CASES = [
     (3, 12, 4, 700, [0, 700, 1], 128),      # group of 3 (not a power of two), an empty sequence
     (2, 16, 2, 5000, [5000, 2049], 2048),   # long chunks: a ragged last one, one key in a chunk
     (2, 16, 2, 9000, [8999, 4097], 4096),   # the longest chunk
+    (4, 16, 2, 4096, [4096, 3000, 1, 0], 4096),   # every sequence fits one chunk: results leave without the epilogue
+    (3, 12, 4, 256, [256, 100, 255], 256),  # the same with groups of 3
+    (2, 16, 2, 700, [700, 200], 512),       # a sequence of two chunks next to one of a single chunk
 ]
 
 
@@ -100,3 +103,26 @@ def test_gqa_rejects_ungrouped_shapes(H):
     with pytest.raises(fdattn.FdError) as e:
         dc.run("fd_decode_attn_gqa")
     assert e.value.status == fdattn.FD_ERR_UNSUPPORTED
+
+
+def test_gqa_single_chunk_sequences_publish_partials_and_recompute(oracle, H):
+    """Sequences of one chunk: the partial sums still reach the workspace, and a head whose guard
+    fires takes the ordinary route (recomputation, then the epilogue) while its neighbours do not."""
+    case = synth.make_case(B=3, Hq=16, Hkv=2, D=128, Smax=2048, seed=430, seq_lens=[2048, 900, 33],
+                           poison_padding=True)
+    planted = synth.plant_keys(case, 2, 36.0, seed=431, allow_shared_kv=True)
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, 2048)
+    assert margin.min() > 1e-2 and 0 < orf.sum() < orf.size
+    dc = H.DeviceCase(case, chunk=2048)
+    got = dc.run("fd_decode_attn_gqa")
+    H.assert_close(got, want, "gqa, single chunk")
+    cf, rf, n, rows = dc.flags()
+    assert np.array_equal(cf, ocf) and np.array_equal(rf, orf) and n == int(orf.sum())
+    # partial sums of the unflagged (head, chunk) pairs are Eq. 4's
+    _, onum, oden = oracle.attn_unified(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"],
+                                        synth.PHI, 2048, return_partials=True)
+    num, den = dc.partials()
+    keep = ~ocf.astype(bool)
+    np.testing.assert_allclose(den[keep], oden[keep], rtol=2e-5, atol=0)
+    np.testing.assert_allclose(num[keep], onum[keep], rtol=0, atol=2e-5 * np.abs(oden[keep]).max())

@@ -80,6 +80,7 @@ def check(H, case, page, chunk, expect_flagged=0):
     (1, 64, 8, 4096, [4000], 256, 1024),               # grouped, long chunks
     (2, 16, 2, 8192, [8191, 4097], 64, 4096),          # the longest chunk over its 64 pages
     (2, 4, 4, 4096, [4096, 2049], 256, 2048),          # per-row kernel, 2048-key chunks
+    (3, 16, 2, 2048, [2048, 777, 1], 64, 2048),        # grouped, one chunk per sequence (no epilogue)
 ])
 def test_paged_matches_oracle_and_contiguous(H, B, Hq, Hkv, Smax, lens, page, chunk):
     case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=8100 + page + chunk, seq_lens=lens,
@@ -109,6 +110,7 @@ def test_paged_flag_and_recompute(H, Hq, Hkv):
     (3, 8, 8, 1024, [0, 1, 1023], 16, 128),            # empty sequence: the new key is the only one
     (2, 32, 32, 2048, [2047, 1000], 256, 1024),        # 8-wavefront workgroups
     (2, 16, 2, 1024, [1000, 512], 32, 256),            # grouped kernel; a fresh page that opens a chunk
+    (2, 16, 2, 1024, [1000, 512], 32, 1024),           # grouped kernel, one chunk per sequence
     (8, 32, 32, 2048, None, 128, 256),                 # every sequence full: nothing appended, second launch
 ])
 def test_paged_append(H, B, Hq, Hkv, Smax, lens, page, chunk):

@@ -9,14 +9,18 @@
 //            heads (zero rows), 4 instructions per block (d = 4 x 32).
 //   weights  P = e^{s S^T - phi} in fp32, in place in the accumulator layout
 //            (lane (head, g) holds keys g, 4+g, 8+g, 12+g of the block) -- Eq. 4, no maximum.
-//            fp16 cannot hold e^{x-phi} over the admissible range of x - phi, so
-//            the second product stays in fp32:
+//            fp16 cannot hold e^{x-phi} over the admissible range of x - phi and bf16 has
+//            8 significant bits, so P goes to the matrix cores as bf16 hi + lo (16 bits),
+//            and V, whose fp16 values have 11, as bf16 hi + lo too (exact):
 //   P.V      out[head][d] += sum_key P[head][key] V[key][d]
-//            v_mfma_f32_16x16x4_f32: A = P (one fp32 per lane: exactly the layout the
-//            score tile leaves behind), B = V converted to fp32.  Lane (n, g) loads
-//            the 16 bytes d = 8n..8n+7 of key 4r+g and feeds element e of them to
-//            accumulator tile e, so V needs no transpose either: 32 instructions
-//            per 16-key block.
+//            v_mfma_f32_16x16x16_bf16, three per tile (hi.hi + hi.lo + lo.hi; lo.lo is below
+//            2^-16 of the term): A = P, whose four weights per lane are exactly contraction
+//            indices 4g..4g+3 when index 4g + r stands for key 4r + g; B = V, where lane
+//            (n, g) loads the 16 bytes d = 8n..8n+7 of the same keys 4r + g (r = 0..3) and
+//            feeds element e of the four rows to accumulator tile e (d = 8n + e), so V needs
+//            no transpose: 24 instructions per 16-key block, an eighth of the matrix-pipe
+//            time of the fp32 16x16x4 form, paid for with about 4 vector-ALU operations
+//            per V element for the split.
 //
 // K reaches the A layout through a per-wavefront LDS tile (coalesced 1 KiB global
 // loads in, 16-byte reads out, XOR-swizzled so both directions are bank-conflict
@@ -48,13 +52,33 @@ struct GqaLds {
     int last;
 };
 
-__device__ __forceinline__ void cvt8(const u32x4 &v, float (&o)[8])
+typedef short bf16x4 __attribute__((ext_vector_type(4)));   // four bf16 bit patterns (an MFMA operand)
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Four floats as bf16 hi + lo: hi = the value truncated to bf16 (its upper 16 bits), lo = what
+// that leaves behind (exact in fp32) as bf16.  An fp16 value has 11 significant bits, so its lo
+// has at most 3 and truncation (EXACT_LO) loses nothing; otherwise lo is rounded to nearest and
+// hi + lo is the value to 2^-17 of its magnitude.
+template <bool EXACT_LO>
+__device__ __forceinline__ void split_bf16(const float (&x)[4], bf16x4 &hi, bf16x4 &lo)
 {
+    uint32_t t[4];
+    float u[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const half2_t h = as_h2(v[i]);
-        o[2 * i] = (float)h.x;
-        o[2 * i + 1] = (float)h.y;
+        t[i] = __builtin_bit_cast(uint32_t, x[i]);
+        u[i] = x[i] - __builtin_bit_cast(float, t[i] & 0xffff0000u);
+    }
+    // v_perm_b32: bytes 2, 3 of the second operand below bytes 2, 3 of the first
+    auto tops = [](float a, float b) { return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a), 0x07060302u); };
+    auto nearest = [](float a, float b) { return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2)); };
+    hi = __builtin_bit_cast(bf16x4, make_uint2(__builtin_amdgcn_perm(t[1], t[0], 0x07060302u), __builtin_amdgcn_perm(t[3], t[2], 0x07060302u)));
+    if constexpr (EXACT_LO) {
+        lo = __builtin_bit_cast(bf16x4, make_uint2(tops(u[0], u[1]), tops(u[2], u[3])));
+    } else {
+        lo = __builtin_bit_cast(bf16x4, make_uint2(nearest(u[0], u[1]), nearest(u[2], u[3])));
     }
 }
 
@@ -125,15 +149,15 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         const int k0 = blk * 16;
         if constexpr (PAGED) {
             // the block holds a resident key (k0 <= last), so a clamped key stays inside it: one page per block
-            const size_t row0 = at.block16(k0);
+            const size_t blk0 = at.block16(k0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + row0 + (size_t)(min(k0 + 4 * i + g, last) - k0) * 16);
+            for (int r = 0; r < 4; ++r) kk[r] = load_stream(kp + blk0 + (size_t)(min(k0 + 4 * r + g, last) - k0) * 16);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + row0 + (size_t)(min(k0 + 4 * r + g, last) - k0) * 16);
+            for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + blk0 + (size_t)(min(k0 + 4 * r + g, last) - k0) * 16);
             return;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) kk[i] = load_stream(kp + at(min(k0 + 4 * i + g, last)));
+        for (int r = 0; r < 4; ++r) kk[r] = load_stream(kp + at(min(k0 + 4 * r + g, last)));
 #pragma unroll
         for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + at(min(k0 + 4 * r + g, last)));
     };
@@ -171,13 +195,29 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
             pw[r] = valid ? e : 0.f;
             den += pw[r];
         }
+        // P as the A operand of the 16x16x16 product: lane (head n, g) holds contraction indices
+        // 4g .. 4g+3, which stand for keys g, 4+g, 8+g, 12+g -- its own four weights.
+        bf16x4 p_hi, p_lo;
+        split_bf16<false>(pw, p_hi, p_lo);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float ve[8];
-            cvt8(vv[r], ve);
+        for (int w = 0; w < 4; ++w) {
+            // dword w of the four V rows: elements d = 8n + 2w (low halves) and 8n + 2w + 1 (high halves)
+            float even[4], odd[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                acc[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(pw[r], ve[e], acc[e], 0, 0, 0);
+            for (int r = 0; r < 4; ++r) {
+                const half2_t h = as_h2(vv[r][w]);
+                even[r] = (float)h.x;
+                odd[r] = (float)h.y;
+            }
+            bf16x4 e_hi, e_lo, o_hi, o_lo;
+            split_bf16<true>(even, e_hi, e_lo);
+            split_bf16<true>(odd, o_hi, o_lo);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_hi, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_hi, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_lo, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_lo, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, e_hi, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, o_hi, acc[2 * w + 1], 0, 0, 0);
         }
     };
     // This wavefront's blocks are wave, wave + 4, ...; nmine of them hold a valid key.

@@ -280,8 +280,13 @@ def main():
     # ---- dominant kernel alone, HIP events on the launch stream ----
     roofline = None
     if entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
-        kname = ("decode_fused_gqa_kernel<%d, false>" % chunk if entry == "fd_decode_attn_gqa" else
-                 "decode_fused_kernel<%d, %s, false>" % (chunk, "true" if run.single_launch else "false"))
+        # template arguments as the profiler prints them: <chunk, paged, wavefronts> for the grouped kernel,
+        # <chunk, in-kernel hand-over, paged, early loads (launches of at most 256 workgroups)> for the per-row one
+        grid = 8 * ((B * Hq + 7) // 8) * ((Smax + chunk - 1) // chunk)
+        early = run.single_launch and grid <= 256
+        kname = ("decode_fused_gqa_kernel<%d, false, 4>" % chunk if entry == "fd_decode_attn_gqa" else
+                 "decode_fused_kernel<%d, %s, false, %s>" % (chunk, "true" if run.single_launch else "false",
+                                                             "true" if early else "false"))
         k_sec = events(run.step if run.single_launch else run.chunk_kernel, args.steps, args.warmup)
         achieved = kv_bytes / k_sec / 1e9
         roofline = {"bound": "hbm", "kernel": kname,

@@ -603,7 +603,7 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_lo
     if (tid == 0) p.ws.row_flags[row] = rf ? 1 : 0;
 }
 
-// The row epilogue for the G <= 16 rows of one head group at once, by 256 threads:
+// The row epilogue for the G <= 16 rows of one head group at once, by 256 threads or more:
 // thread (h, t) = (tid / 32, tid % 32) owns elements 4t..4t+3 of row row0 + h and walks
 // that row's nb partial results in chunk order with a running maximum of the
 // references (Eq. 2; every factor is exactly 1 for an unflagged row, which makes it
@@ -624,7 +624,7 @@ __device__ __forceinline__ void rows_epilogue(const Problem &p, int row0, int G,
             return *static_cast<const u32x4 *>(ptr);
         }
     };
-    for (int h = tid >> 5; h < G; h += 8) {
+    for (int h = tid >> 5; h < G; h += (int)(blockDim.x >> 5)) {
         const int row = row0 + h;
         const int nb = nb_of(row);
         if (nb <= 0) {                          // (only a launch of its own gets here: empty sequence)

@@ -37,18 +37,17 @@ namespace {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGqaThreads = 256;
-constexpr int kTileFloats = 4 * 16 * kHeadDim;   // [wave][head][d] reduction tile, 32 KiB
-
+// NW wavefronts per workgroup (4 or 8; the launcher uses 4).
+template <int NW>
 struct GqaLds {
-    // K staging (4 wavefronts x 4 KiB) during the main loop, then the reduction tile,
-    // then (rarely) the per-row recomputation's workspace: never live together.
-    alignas(16) float tile[kTileFloats];
-    float den[4][64];
+    // K staging (NW wavefronts x 4 KiB) during the main loop, then the reduction tile
+    // [wave][head][d] (NW x 8 KiB), then (rarely) the per-row recomputation's workspace:
+    // never live together.
+    alignas(16) float tile[NW * 16 * kHeadDim];
+    float den[NW][64];
     float e_new[16];                 // weight of an appended key per head (0 when there is none)
     int   f_new[16];                 // ... and whether it left the bounds
-    unsigned long long bad[4];
-    float red[4];
+    unsigned long long bad[NW];
     int last;
 };
 
@@ -82,11 +81,14 @@ __device__ __forceinline__ void split_bf16(const float (&x)[4], bf16x4 &hi, bf16
     }
 }
 
-template <int C, bool PAGED = false>
-__global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const Problem p)
+template <int C, bool PAGED = false, int NW = 4>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_kernel(const Problem p)
 {
-    static_assert(sizeof(ChunkLds<4, C>) <= sizeof(float) * kTileFloats, "recompute workspace must fit the tile");
-    __shared__ GqaLds lds;
+    static_assert(NW == 4 || NW == 8, "the appended key's lane assignment covers 16 heads with 4 wavefronts");
+    static_assert(sizeof(ChunkLds<NW, C>) <= sizeof(GqaLds<NW>::tile), "recompute workspace must fit the tile");
+    constexpr int kGqaThreads = NW * 64;
+    constexpr int UP = C / (4 * NW) < 8 ? C / (4 * NW) : 8;    // stage depth of the per-row recomputation
+    __shared__ GqaLds<NW> lds;
     constexpr int NBLK = C / 16;               // 16-key blocks in the chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, g = lane >> 4;    // n: head (scores) / 16-byte segment (loads); g: lane group
@@ -94,8 +96,10 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
 
     // All chunks of a KV-head group go to the same XCD (see decode_fused_kernel).
     const int groups = p.B * p.Hkv;
+    // chunk-major, so that chunks past the end of the sequences come last (see decode_fused_kernel)
+    const int groups8 = (groups + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int gi = (blockIdx.x & 7) + 8 * (j / p.nc), c = j % p.nc;
+    const int c = j / groups8, gi = (blockIdx.x & 7) + 8 * (j - c * groups8);
     if (gi >= groups) return;
     const int b = gi / p.Hkv;
     const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group
@@ -220,35 +224,35 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
             acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, o_hi, acc[2 * w + 1], 0, 0, 0);
         }
     };
-    // This wavefront's blocks are wave, wave + 4, ...; nmine of them hold a valid key.
+    // This wavefront's blocks are wave, wave + NW, ...; nmine of them hold a valid key.
     // Two-stage software pipeline, steady state free of branches around loads.
     const int nblk_valid = min(NBLK, (nres + 15) / 16);
-    const int nmine = nblk_valid > wave ? (nblk_valid - wave + 3) / 4 : 0;
+    const int nmine = nblk_valid > wave ? (nblk_valid - wave + NW - 1) / NW : 0;
     if (nmine > 0) {
         u32x4 kA[4], vA[4], kB[4], vB[4];
         issue(wave, kA, vA);
         int i = 0;
 #pragma unroll 1
         for (; i + 2 < nmine; i += 2) {
-            issue(wave + 4 * (i + 1), kB, vB);
+            issue(wave + NW * (i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of the arithmetic
-            reduce(wave + 4 * i, kA, vA);
-            issue(wave + 4 * (i + 2), kA, vA);
+            reduce(wave + NW * i, kA, vA);
+            issue(wave + NW * (i + 2), kA, vA);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + 4 * (i + 1), kB, vB);
+            reduce(wave + NW * (i + 1), kB, vB);
         }
         if (i + 2 == nmine) {
-            issue(wave + 4 * (i + 1), kB, vB);
+            issue(wave + NW * (i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + 4 * i, kA, vA);
-            reduce(wave + 4 * (i + 1), kB, vB);
+            reduce(wave + NW * i, kA, vA);
+            reduce(wave + NW * (i + 1), kB, vB);
         } else {
-            reduce(wave + 4 * i, kA, vA);
+            reduce(wave + NW * i, kA, vA);
         }
     }
 
     // ---- the appended key, if this chunk takes it: one more term of Eq. 4 per head ----
-    // Lane group (wave, g) handles head 4 wave + g on the vector ALU: weight e^{x - phi}
+    // Lane group (wave, g) of the first four wavefronts handles head 4 wave + g on the vector ALU: weight e^{x - phi}
     // and guard from the step's own K row.  The weights go to LDS and enter the sums at
     // the reduction below, multiplied with the step's V row.
     float e_new = 0.f;
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         const u32x4 kn = reinterpret_cast<const u32x4 *>(p.k_new + at_new)[n];
         const u32x4 qh = reinterpret_cast<const u32x4 *>(p.q + (size_t)(row0 + min(hh, G - 1)) * kHeadDim)[n];
         const float d = row16_sum(dot8(qh, kn)) * scale + nphi;
-        if (hh < G) {
+        if (hh < G) {                          // (never for a wavefront past the fourth: hh >= 16)
             f_new = !((d > lo) & (d < hi));
             e_new = __builtin_amdgcn_exp2f(d * kLog2e);
         }
@@ -287,9 +291,11 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     }
     lds.den[wave][lane] = den;
     if (lane == 0) lds.bad[wave] = bad_mask;
-    if (n == 0) { lds.e_new[4 * wave + g] = e_new; lds.f_new[4 * wave + g] = f_new; }
+    if (n == 0 && wave < 4) { lds.e_new[4 * wave + g] = e_new; lds.f_new[4 * wave + g] = f_new; }
     __syncthreads();
-    const unsigned long long any = lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3];
+    unsigned long long any = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) any |= lds.bad[w];
     // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
     unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
 #pragma unroll
@@ -297,7 +303,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     auto den_of = [&](int h) {                 // Eq. 4's denominator of head h over this chunk
         float s = lds.e_new[h];
 #pragma unroll
-        for (int w = 0; w < 4; ++w)
+        for (int w = 0; w < NW; ++w)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) s += lds.den[w][h + 16 * q4];
         return s;
@@ -308,13 +314,14 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
     const bool solo = p.elect && nb == 1 && !flagged_heads;
     // 4 consecutive elements per thread: one 16-byte LDS read per wavefront tile, 16 bytes out
     for (int i = 4 * tid; i < G * kHeadDim; i += 4 * kGqaThreads) {
-        const float4 a = *reinterpret_cast<const float4 *>(&lds.tile[i]);
-        const float4 b = *reinterpret_cast<const float4 *>(&lds.tile[16 * kHeadDim + i]);
-        const float4 cc = *reinterpret_cast<const float4 *>(&lds.tile[32 * kHeadDim + i]);
-        const float4 d = *reinterpret_cast<const float4 *>(&lds.tile[48 * kHeadDim + i]);
+        float4 o = *reinterpret_cast<const float4 *>(&lds.tile[i]);
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {         // wavefront order
+            const float4 t = *reinterpret_cast<const float4 *>(&lds.tile[w * 16 * kHeadDim + i]);
+            o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+        }
         const int q = i & (kHeadDim - 1);      // LDS position -> element index (see the layout above)
         const int d0 = 2 * (q & 63) + 4 * (q >> 6);
-        float4 o = make_float4(a.x + b.x + cc.x + d.x, a.y + b.y + cc.y + d.y, a.z + b.z + cc.z + d.z, a.w + b.w + cc.w + d.w);
         if (owner) {                           // + e_new[head] * v_new[d0 .. d0 + 3]
             const float en = lds.e_new[i / kHeadDim];
             const uint2 vn = *reinterpret_cast<const uint2 *>(p.v_new + (size_t)gi * kHeadDim + d0);
@@ -355,7 +362,7 @@ __global__ __launch_bounds__(kGqaThreads, 3) void decode_fused_gqa_kernel(const 
         for (int h = 0; h < G; ++h) {
             if (!((flagged_heads >> h) & 1)) continue;
             __syncthreads();
-            chunk_body<C, 4, (C / 16 < 8 ? C / 16 : 8), true, C, false, PAGED>(p, row0 + h, c, *reinterpret_cast<ChunkLds<4, C> *>(lds.tile));
+            chunk_body<C, NW, UP, true, C, false, PAGED>(p, row0 + h, c, *reinterpret_cast<ChunkLds<NW, C> *>(lds.tile));
         }
     }
 
@@ -375,8 +382,11 @@ template <int C> struct GqaLauncher {
         const long long groups = (long long)p.B * p.Hkv;
         const unsigned grid = (unsigned)(8ll * ((groups + 7) / 8) * p.nc);
         if (grid == 0) return hipSuccess;
-        if (p.block_table) return launch(decode_fused_gqa_kernel<C, true>, dim3(grid), dim3(kGqaThreads), s, p);
-        return launch(decode_fused_gqa_kernel<C>, dim3(grid), dim3(kGqaThreads), s, p);
+        // 4 wavefronts per workgroup.  (8 were measured for launches of at most one workgroup per
+        // compute unit: within 2 % either way at 256 workgroups, 12 % faster only for a lone
+        // 4096-key chunk, which fd_pick_chunk never chooses.)
+        if (p.block_table) return launch(decode_fused_gqa_kernel<C, true, 4>, dim3(grid), dim3(256), s, p);
+        return launch(decode_fused_gqa_kernel<C, false, 4>, dim3(grid), dim3(256), s, p);
     }
 };
 

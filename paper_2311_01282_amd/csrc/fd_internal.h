@@ -8,6 +8,7 @@
 
 namespace fd {
 
+constexpr int kComputeUnits = 256; // of an MI355X
 constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
 constexpr float kLog2e = 1.4426950408889634f;
 

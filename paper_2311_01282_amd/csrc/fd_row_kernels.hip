@@ -24,11 +24,18 @@ template <int C> struct Tune {
     static constexpr int UP = NG < 4 ? NG : 4;
 };
 
-// ELECT: the launch is small enough for the in-kernel hand-over (and for early loads).
+// ELECT: the launch is small enough for the in-kernel hand-over.
 // PAGED: K and V are page pools addressed through the sequence's block table.
-template <int C, bool ELECT, bool PAGED = false>
+// EARLY: the first loads go out before the sequence length has arrived -- for launches of at
+//        most one workgroup per compute unit, where every workgroup starts with the launch and
+//        the length load is on its critical path.  In a larger launch the later workgroups
+//        start behind somebody else's stream anyway, and where the launch covers more than the
+//        sequences hold (max_seq beyond the lengths) many of them are chunks without keys,
+//        which then leave without reading any.
+template <int C, bool ELECT, bool PAGED = false, bool EARLY = false>
 __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Problem p)
 {
+    static_assert(!EARLY || (ELECT && !PAGED), "early loads: in-kernel hand-over, contiguous cache");
     constexpr int NW = Tune<C>::NW, UP = Tune<C>::UP;
     __shared__ ChunkLds<NW, C> lds;
     const int tid = threadIdx.x;
@@ -37,11 +44,18 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     // go to the same XCD (row % 8), so the row's counters and partial results stay
     // in one L2 instead of bouncing between eight.  Placement only affects speed:
     // every hand-over below is device-coherent wherever the workgroups land.
+    // Order within that: chunk-major -- chunk 0 of every row, then chunk 1, ... -- so that the
+    // chunks past the end of the sequences (the launch covers max_seq) are dispatched last and
+    // leave at once, instead of taking a compute unit's first slot while another unit gets two
+    // full chunks.  (Against row-major, measured: 32.5 -> 25.8 us for 8192 keys in a cache of
+    // 8208, 107 -> 89 us for the grouped kernel on 32 sequences of 4096 in a cache of 8192,
+    // 4 % faster on large uniform batches, 2 % slower on the ragged batch of 16.)
+    const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int row = (blockIdx.x & 7) + 8 * (j / p.nc), c = j % p.nc;
+    const int c = j / groups8, row = (blockIdx.x & 7) + 8 * (j - c * groups8);
     if (row >= p.rows) return;
     int S;
-    const bool flagged = chunk_body<C, NW, UP, false, C, ELECT && !PAGED, PAGED>(p, row, c, lds, &S);
+    const bool flagged = chunk_body<C, NW, UP, false, C, EARLY, PAGED>(p, row, c, lds, &S);
     const int nb = (S + C - 1) / C;            // chunks of this row that hold a valid key
     if (c >= nb) {                             // padding chunk: zero partials were written
         if (nb == 0 && c == 0 && ELECT) {    // empty sequence: nobody else owns the row
@@ -121,6 +135,8 @@ template <int C> struct FusedLauncher {
         if (p.block_table)
             return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                            : launch(decode_fused_kernel<C, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
+        if (p.elect && grid <= (unsigned)kComputeUnits)
+            return launch(decode_fused_kernel<C, true, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
         return p.elect ? launch(decode_fused_kernel<C, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                        : launch(decode_fused_kernel<C, false>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
     }

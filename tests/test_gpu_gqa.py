@@ -39,11 +39,15 @@ CASES = [
     (4, 16, 2, 4096, [4096, 3000, 1, 0], 4096),   # every sequence fits one chunk: results leave without the epilogue
     (3, 12, 4, 256, [256, 100, 255], 256),  # the same with groups of 3
     (2, 16, 2, 700, [700, 200], 512),       # a sequence of two chunks next to one of a single chunk
+    (8, 64, 8, 1024, [1024, 100, 300, 1, 0, 513, 512, 900], 256),   # 256 workgroups, ragged: many chunks past the ends
+    (10, 64, 8, 1024, None, 256),           # 320 workgroups: the row epilogue as a second launch
 ]
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,Smax,lens,chunk", CASES)
 def test_gqa_matches_oracle_and_per_row_path(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
+    if lens is None:
+        lens = [Smax - 53 * b for b in range(B)]
     case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=400 + Smax + chunk, seq_lens=lens,
                            poison_padding=True)
     want = exact(oracle, case)

@@ -31,6 +31,9 @@ SMALL = [
     (1, 8, 2, 700, [700], 128),                       # grouped heads through the per-row path
     (2, 4, 4, 5000, [5000, 2049], 2048),              # long chunks: a ragged last one, one key in a chunk
     (2, 4, 4, 9000, [8999, 4097], 4096),              # the longest chunk
+    (2, 32, 32, 2048, [1500, 900], 256),              # 512 workgroups: in-kernel hand-over without early loads
+    (3, 32, 32, 1024, [1024, 1, 300], 128),           # 768 workgroups, most of them past the sequences' ends
+    (1, 16, 16, 4096, [700], 256),                    # 256 workgroups (early loads), a cache six times the sequence
 ]
 
 

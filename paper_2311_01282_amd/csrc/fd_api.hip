@@ -26,10 +26,7 @@ fd_status plan(const fd_shape *sh, Layout *L)
     if (sh->n_q_heads % sh->n_kv_heads != 0) return FD_ERR_SHAPE;
     if (!std::isfinite(sh->scale)) return FD_ERR_SHAPE;
     if (sh->head_dim != fd::kHeadDim) return FD_ERR_UNSUPPORTED;
-    switch (sh->chunk) {
-        case 64: case 128: case 256: case 512: case 1024: case 2048: case 4096: break;
-        default: return FD_ERR_UNSUPPORTED;
-    }
+    if (sh->chunk < 64 || sh->chunk > 4096 || sh->chunk % 16 != 0) return FD_ERR_UNSUPPORTED;
     const long long rows = (long long)sh->batch * sh->n_q_heads;
     const long long nc = ((long long)sh->max_seq + sh->chunk - 1) / sh->chunk;
     if (rows * nc >= (1ll << 31)) return FD_ERR_UNSUPPORTED;
@@ -190,16 +187,20 @@ int32_t fd_pick_chunk(const fd_shape *shape)
         return 0;
     };
     int32_t c = 0;
+    auto fill_of = [](long long w) { return (double)w / (256.0 * (double)((w + 255) / 256)); };
     if (grouped) {
-        // the longest chunk whose workgroups fill whole rounds of the 256 CUs to 90 % (384 workgroups
-        // would leave half the chip idle in their second round: 139 us against 128 us with 768)
+        // the fewest (longest, equal) chunks whose workgroups fill whole rounds of the 256 CUs to 90 %
+        // (384 workgroups would leave half the chip idle in their second round: 139 us against 128 us
+        // with 768); a length is a multiple of 16 keys, not necessarily a power of two
         double best = 0.0;
-        for (int32_t cand : sizes) {
-            const long long w = workgroups(cand);
+        for (long long nb = ((long long)sh.max_seq + 4095) / 4096; nb <= ((long long)sh.max_seq + 63) / 64; ++nb) {
+            const long long len = (((long long)sh.max_seq + nb - 1) / nb + 15) / 16 * 16;
+            if (len < 64) break;
+            const long long w = workgroups((int32_t)len);
             if (w < 256) continue;
-            const double fill = (double)w / (256.0 * (double)((w + 255) / 256));
-            if (fill >= 0.9) { c = cand; break; }
-            if (fill > best) { best = fill; c = cand; }
+            const double fill = fill_of(w);
+            if (fill >= 0.9) { c = (int32_t)len; break; }
+            if (fill > best) { best = fill; c = (int32_t)len; }
         }
     } else {
         const int32_t quarter = sh.max_seq / 4;
@@ -208,7 +209,26 @@ int32_t fd_pick_chunk(const fd_shape *shape)
         if (!c) c = largest_with(256, 64, longest);
     }
     if (!c) c = largest_with(256, 64, grouped ? 4096 : 1024);
-    return c ? c : 64;
+    if (!c) c = 64;
+    // A launch of one to four rounds of the chip that leaves its last round less than 90 % full
+    // (288 workgroups: 32 CUs stream two chunks while 224 wait) gets chunks of equal length, a
+    // multiple of 16 keys that need not be a power of two, in the number that fills whole rounds:
+    // 32 rows of 9216 keys run as 8 x 1152 keys instead of 9 x 1024 (34.8 -> 27 us).  Fewest (longest)
+    // chunks first, within a factor of two of the choice above.
+    const long long w0 = workgroups(c);
+    if (w0 > 256 && w0 <= 1024 && fill_of(w0) < 0.9) {
+        const long long nb0 = ((long long)sh.max_seq + c - 1) / c;
+        const int32_t cap = grouped ? 4096 : 2048;
+        double best = fill_of(w0);
+        for (long long nb = nb0 / 2 > 0 ? nb0 / 2 : 1; nb <= 2 * nb0; ++nb) {
+            const long long len = (((long long)sh.max_seq + nb - 1) / nb + 15) / 16 * 16;
+            if (len < 64 || len > cap) continue;
+            const double fill = fill_of(workgroups((int32_t)len));
+            if (fill >= 0.9) { c = (int32_t)len; break; }
+            if (fill > best + 0.05) { best = fill; c = (int32_t)len; }
+        }
+    }
+    return c;
 }
 
 // The chunk kernel of fd_decode_attn / fd_decode_attn_gqa alone: no election, no
@@ -324,7 +344,10 @@ static fd_status set_paged(fd::Problem *p, const fd_shape *shape, const int32_t 
     if (((uintptr_t)block_table % 4) != 0) return FD_ERR_SHAPE;
     // a power of two; a chunk may span at most 64 pages (one table entry per lane)
     if (page_size < 16 || (page_size & (page_size - 1)) != 0 || n_pages < 1 || shape->max_seq % page_size != 0 ||
-        shape->chunk > 64 * (long long)page_size)
+        // a chunk's pages are looked up by the 64 lanes of a wavefront; a chunk that neither divides
+        // nor is divided by the page may start anywhere in one (at a multiple of 16)
+        (shape->chunk % page_size == 0 || page_size % shape->chunk == 0 ? shape->chunk : shape->chunk + page_size - 16) >
+            64 * (long long)page_size)
         return FD_ERR_SHAPE;
     p->block_table = block_table;
     p->pages_per_seq = shape->max_seq / page_size;

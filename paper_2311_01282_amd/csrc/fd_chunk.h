@@ -234,7 +234,8 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     const int hkv = hq / p.G;
     int S_raw = 0;
     if constexpr (EARLY) S_raw = seq_len_issue(p, b);
-    const int start = c * C;
+    const int len = p.C;                       // keys per chunk (<= C, the kernel's capacity)
+    const int start = c * len;
     const size_t slot = (size_t)row * p.nc + c;
 
     const u32x4 qv = reinterpret_cast<const u32x4 *>(p.q + (size_t)row * kHeadDim)[seg];
@@ -245,7 +246,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     auto key_of = [&](int g) { return (g * NW + wave) * 4 + sub; };
     u32x4 kA[UP], vA[UP];
     if constexpr (EARLY) {
-        const int cap = min(C, p.Smax - start) - 1;   // the chunk's last key inside the buffer (start < Smax)
+        const int cap = min(len, p.Smax - start) - 1;   // the chunk's last key inside the buffer (start < Smax)
 #pragma unroll
         for (int u = 0; u < UP; ++u) kA[u] = load_stream(kp + at(min(key_of(u), cap)));
 #pragma unroll
@@ -256,11 +257,11 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
     const int S_res = EARLY ? seq_len_finish(p, S_raw) : clamp_len(p, p.seq_lens[b]);
     const int S = effective_len(p, S_res);
     if (len_out) *len_out = S;
-    const int nvalid = min(C, S - start);      // <= 0: no valid key in this chunk
-    const int nres = min(C, S_res - start);    // of them resident in the cache
+    const int nvalid = min(len, S - start);    // <= 0: no valid key in this chunk
+    const int nres = min(len, S_res - start);  // of them resident in the cache
     // A fused append puts the new key at offset jn of exactly one chunk of the row.
     const int jn = S_res - start;
-    const bool owner = (S != S_res) & (jn >= 0) & (jn < C);
+    const bool owner = (S != S_res) & (jn >= 0) & (jn < len);
     // where the appended row goes (all lanes take part in the page lookup of a paged cache)
     const size_t row_new = at.absolute(owner ? jn : 0);
     // With early loads an empty chunk takes the ordinary path below (no block beyond the

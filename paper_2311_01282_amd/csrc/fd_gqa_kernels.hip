@@ -105,11 +105,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group
     const int S_res = clamp_len(p, p.seq_lens[b]);          // keys resident in the cache
     const int S = effective_len(p, S_res);                  // plus the appended one, if any
-    const int nb = (S + C - 1) / C;
-    const int start = c * C;
-    const int nvalid = min(C, S - start);
-    const int nres = min(C, S_res - start);
-    const bool owner = (S != S_res) & (S_res >= start) & (S_res < start + C);   // this chunk takes the appended key
+    const int len = p.C;                                    // keys per chunk (<= C, the kernel's capacity)
+    const int nb = (S + len - 1) / len;
+    const int start = c * len;
+    const int nvalid = min(len, S - start);
+    const int nres = min(len, S_res - start);
+    const bool owner = (S != S_res) & (S_res >= start) & (S_res < start + len);   // this chunk takes the appended key
 
     if (nvalid <= 0) {                         // padding chunk: zero partials, no flag
         for (int i = tid; i < G * kHeadDim; i += kGqaThreads)
@@ -394,7 +395,7 @@ template <int C> struct GqaLauncher {
 
 hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s)
 {
-    switch (p.C) {
+    switch (chunk_capacity(p.C)) {
         case 64:   return GqaLauncher<64>::run(p, s);
         case 128:  return GqaLauncher<128>::run(p, s);
         case 256:  return GqaLauncher<256>::run(p, s);

@@ -10,6 +10,15 @@ namespace fd {
 
 constexpr int kComputeUnits = 256; // of an MI355X
 constexpr int kHeadDim = 128;      // fp16 elements per K/V row = 256 bytes = 16 x 16-byte segments
+
+// Chunk lengths are multiples of 16 from 64 to 4096 keys; the kernels are compiled for these
+// capacities and a chunk runs on the smallest one that holds it.
+inline int chunk_capacity(int len)
+{
+    int cap = 64;
+    while (cap < len) cap *= 2;
+    return cap;
+}
 constexpr float kLog2e = 1.4426950408889634f;
 
 // One record per (row, chunk) slot, read by the row epilogue with a single 16-byte

@@ -56,7 +56,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     if (row >= p.rows) return;
     int S;
     const bool flagged = chunk_body<C, NW, UP, false, C, EARLY, PAGED>(p, row, c, lds, &S);
-    const int nb = (S + C - 1) / C;            // chunks of this row that hold a valid key
+    const int nb = (S + p.C - 1) / p.C;        // chunks of this row that hold a valid key
     if (c >= nb) {                             // padding chunk: zero partials were written
         if (nb == 0 && c == 0 && ELECT) {    // empty sequence: nobody else owns the row
             if (tid < kHeadDim) p.out[(size_t)row * kHeadDim + tid] = 0;
@@ -166,17 +166,17 @@ template <int C> struct SyncLauncher {
 
 hipError_t launch_decode_fused(const Problem &p, hipStream_t s)
 {
-    return dispatch_chunk<FusedLauncher>(p.C, p, s);
+    return dispatch_chunk<FusedLauncher>(chunk_capacity(p.C), p, s);
 }
 
 hipError_t launch_partial_unified(const Problem &p, hipStream_t s)
 {
-    return dispatch_chunk<UnifiedLauncher>(p.C, p, s);
+    return dispatch_chunk<UnifiedLauncher>(chunk_capacity(p.C), p, s);
 }
 
 hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s)
 {
-    return dispatch_chunk<SyncLauncher>(p.C, p, use_list, s);
+    return dispatch_chunk<SyncLauncher>(chunk_capacity(p.C), p, use_list, s);
 }
 
 }  // namespace fd

@@ -44,7 +44,12 @@ def test_workspace_bytes(fdattn):
     assert need <= n <= need + 16 * 256 and n % 256 == 0
     # unsupported or invalid shapes give 0
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0     # head_dim
-    assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 8192, 100, 0.1)) == 0    # chunk
+    for chunk in (100, 72, 48, 4112, 0, -64):                                                  # chunk: a multiple of 16 in [64, 4096]
+        assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 8192, chunk, 0.1)) == 0
+    for chunk in (64, 80, 1152, 3008, 4096):
+        nc = -(-8192 // chunk)
+        n = fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 8192, chunk, 0.1))
+        assert n >= 32 * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4)
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0     # heads
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 0, 256, 0.1)) == 0       # max_seq
     # a ragged last chunk still gets a slot
@@ -127,7 +132,7 @@ def test_status_strings_and_getters(fdattn):
         fdattn.fd_get_flags(sh, base, 16)
 
 
-def test_pick_chunk_is_a_supported_size_and_ignores_the_chunk_field(fdattn):
+def test_pick_chunk_on_the_benchmark_shapes_ignores_the_chunk_field(fdattn):
     from paper_2311_01282_amd import synth
     for name, cfg in synth.CONFIGS.items():
         picks = set()
@@ -136,29 +141,43 @@ def test_pick_chunk_is_a_supported_size_and_ignores_the_chunk_field(fdattn):
             picks.add(fdattn.fd_pick_chunk(sh))
         assert len(picks) == 1, name
         c = picks.pop()
-        assert c in (64, 128, 256, 512, 1024, 2048, 4096), name
+        assert c in (64, 128, 256, 512, 1024, 2048, 4096), name     # (the benchmark shapes are powers of two)
         assert c <= 1024 or cfg["Hq"] != cfg["Hkv"], name          # long chunks are for grouped heads only
         # the picked size is accepted by the sizing call
         assert fdattn.fd_workspace_bytes(fdattn.make_shape(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"], c, 0.1)) > 0
 
 
 def test_pick_chunk_fills_the_chip_when_the_shape_allows_it(fdattn):
-    # one workgroup per (row or head group, chunk): at least 256 of them when any supported size gives that many
+    # one workgroup per (row or head group, chunk): at least 256 of them when any supported length gives that many
+    fill = lambda w: w / (256.0 * -(-w // 256))
     for (B, Hq, Hkv, Smax) in [(1, 32, 32, 1024), (1, 32, 32, 8192), (16, 32, 32, 4096), (32, 64, 8, 4096),
                                (4, 32, 32, 32768), (1, 8, 8, 300), (1, 1, 1, 64), (3, 40, 40, 5000), (8, 64, 8, 4096),
-                               (64, 64, 8, 4096), (1, 64, 8, 32768), (2, 32, 8, 8192), (48, 64, 8, 4096), (5, 40, 8, 4096)]:
+                               (64, 64, 8, 4096), (1, 64, 8, 32768), (2, 32, 8, 8192), (48, 64, 8, 4096), (5, 40, 8, 4096),
+                               (1, 32, 32, 9216), (1, 32, 32, 10000), (2, 32, 32, 5000), (8, 64, 8, 5000), (1, 64, 8, 40000),
+                               (32, 64, 8, 4112), (3, 64, 8, 777)]:
         c = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, 0.1))
         units = B * (Hkv if Hq != Hkv else Hq)
         wgs = lambda cc: units * (-(-Smax // cc))
-        assert c in (64, 128, 256, 512, 1024, 2048, 4096)
+        assert 64 <= c <= 4096 and c % 16 == 0
+        assert fdattn.fd_workspace_bytes(fdattn.make_shape(B, Hq, Hkv, 128, Smax, c, 0.1)) > 0
         if Hq != Hkv and wgs(c) >= 256 and c < 4096:
-            # grouped: the longest chunk that still fills the chip, whole rounds of it
-            fill = lambda cc: wgs(cc) / (256.0 * -(-wgs(cc) // 256))
-            assert wgs(2 * c) < 256 or fill(2 * c) < 0.9, (B, Hq, Hkv, Smax, c)
+            # grouped: the fewest equal chunks that fill whole rounds of the chip -- one chunk fewer does not
+            nb = -(-Smax // c)
+            if nb > 1:
+                longer = -(-(-(-Smax // (nb - 1))) // 16) * 16
+                assert longer > 4096 or wgs(longer) < 256 or fill(wgs(longer)) < 0.9, (B, Hq, Hkv, Smax, c)
         if wgs(64) >= 256:
-            assert wgs(c) >= 256, (B, Hq, Hkv, Smax, c)
+            assert wgs(c) >= 0.9 * 256, (B, Hq, Hkv, Smax, c)
+            # a launch of up to four rounds of the chip fills its last round
+            if wgs(c) <= 1024:
+                assert fill(wgs(c)) >= 0.9, (B, Hq, Hkv, Smax, c, wgs(c))
         else:
             assert c == 64
+    # the shapes the sweeps were fitted on keep their power-of-two picks; lengths between them get equal chunks
+    for shape, want in (((1, 32, 32, 8192), 1024), ((32, 64, 8, 4096), 4096), ((16, 64, 8, 4096), 2048), ((8, 64, 8, 4096), 1024),
+                        ((16, 32, 32, 4096), 512), ((4, 32, 32, 32768), 1024), ((1, 32, 32, 9216), 1152), ((1, 32, 32, 12288), 1536),
+                        ((8, 64, 8, 5000), 1264), ((32, 64, 8, 4112), 2064)):
+        assert fdattn.fd_pick_chunk(fdattn.make_shape(*shape[:3], 128, shape[3], 0, 0.1)) == want, shape
     # invalid shapes give 0
     assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0
     assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0

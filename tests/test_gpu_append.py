@@ -82,6 +82,8 @@ def check(oracle, H, case, chunk, k_new=None, v_new=None, seed=1, expect_flagged
     (1, 34, 2, 300, [299], 64),                       # groups of 17: per-row kernel with shared KV heads
     (3, 16, 2, 512, [300, 510, 0], 512),              # grouped, one chunk per sequence: no epilogue; new key alone
     (2, 16, 2, 1024, [512, 511], 512),                # grouped: the new key opens a second chunk / completes the only one
+    (3, 4, 4, 1200, [575, 576, 1151], 576),           # chunks of 576 keys: last key of a chunk, first of the next
+    (3, 16, 2, 1200, [575, 576, 1151], 576),          # the same through the grouped kernel
 ])
 def test_append_matches_concatenate_then_attend(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
     if lens is None:

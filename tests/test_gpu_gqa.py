@@ -41,6 +41,9 @@ CASES = [
     (2, 16, 2, 700, [700, 200], 512),       # a sequence of two chunks next to one of a single chunk
     (8, 64, 8, 1024, [1024, 100, 300, 1, 0, 513, 512, 900], 256),   # 256 workgroups, ragged: many chunks past the ends
     (10, 64, 8, 1024, None, 256),           # 320 workgroups: the row epilogue as a second launch
+    (2, 16, 2, 3000, [3000, 1111], 1152),   # a chunk length that is no power of two (capacity 2048)
+    (1, 8, 2, 600, [555], 80),              # ... of 80 keys (capacity 128)
+    (2, 16, 2, 9000, [8999, 4097], 3008),   # ... of 3008 keys (capacity 4096)
 ]
 
 
@@ -82,7 +85,7 @@ def test_gqa_partial_sums_match_eq4(oracle, H):
     assert (np.abs(num - onum) <= num_bound(case, oden)[..., None]).all()
 
 
-@pytest.mark.parametrize("Smax,lens,chunk", [(2048, [2048, 1111], 256), (8192, [8192, 5000], 4096)])
+@pytest.mark.parametrize("Smax,lens,chunk", [(2048, [2048, 1111], 256), (8192, [8192, 5000], 4096), (3000, [3000, 1700], 1152)])
 def test_gqa_flags_are_per_query_head_and_rows_recomputed(oracle, H, Smax, lens, chunk):
     case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=Smax, seed=420, seq_lens=lens,
                            poison_padding=True)

@@ -63,7 +63,7 @@ def check(H, case, page, chunk, expect_flagged=0):
     entry = "fd_decode_attn_gqa" if 2 <= case["Hq"] // case["Hkv"] <= 16 else "fd_decode_attn"
     same = pc.dc.run(entry)
     step = np.maximum(np.abs(same), 2.0 ** -14) * 2.0 ** -10          # fp16 spacing at that magnitude
-    assert (np.abs(got - same) <= step).all() and (got != same).mean() < 1e-3
+    assert (np.abs(got - same) <= step).all() and (got != same).sum() <= max(1, 1e-3 * got.size)
     return got
 
 
@@ -81,6 +81,10 @@ def check(H, case, page, chunk, expect_flagged=0):
     (2, 16, 2, 8192, [8191, 4097], 64, 4096),          # the longest chunk over its 64 pages
     (2, 4, 4, 4096, [4096, 2049], 256, 2048),          # per-row kernel, 2048-key chunks
     (3, 16, 2, 2048, [2048, 777, 1], 64, 2048),        # grouped, one chunk per sequence (no epilogue)
+    (2, 4, 4, 3072, [3000, 1700], 64, 1152),           # chunks of 1152 keys = 18 pages
+    (2, 4, 4, 3072, [3000, 1700], 256, 1152),          # ... that start in the middle of a page
+    (2, 16, 2, 3072, [3000, 1700], 256, 1152),         # ... through the grouped kernel
+    (1, 4, 4, 2048, [2000], 16, 1008),                 # 63 pages per chunk
 ])
 def test_paged_matches_oracle_and_contiguous(H, B, Hq, Hkv, Smax, lens, page, chunk):
     case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=8100 + page + chunk, seq_lens=lens,
@@ -204,9 +208,10 @@ def test_paged_rejects_bad_arguments():
         with pytest.raises(fdattn.FdError) as e:
             fdattn.fd_decode_attn_paged(*args)
         assert e.value.status == code
-    # more than 64 pages per chunk
-    sh2 = fdattn.make_shape(1, 2, 2, 128, 2048, 1024, 0.1)
-    n2 = fdattn.fd_workspace_bytes(sh2)
-    with pytest.raises(fdattn.FdError) as e:
-        fdattn.fd_decode_attn_paged(sh2, p, p, p, p, 8, 16, p, 3.0, (-60.0, 20.0), p, p, n2)
-    assert e.value.status == fdattn.FD_ERR_SHAPE
+    # more than 64 pages per chunk: 128; 65; 63 and a bit when the chunk may start inside a page
+    for chunk, page in ((2048, 16), (1040, 16), (4080, 64)):
+        sh2 = fdattn.make_shape(1, 2, 2, 128, 4096, chunk, 0.1)
+        n2 = fdattn.fd_workspace_bytes(sh2)
+        with pytest.raises(fdattn.FdError) as e:
+            fdattn.fd_decode_attn_paged(sh2, p, p, p, p, page, 16, p, 3.0, (-60.0, 20.0), p, p, n2)
+        assert e.value.status == fdattn.FD_ERR_SHAPE

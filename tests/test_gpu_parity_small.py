@@ -34,6 +34,9 @@ SMALL = [
     (2, 32, 32, 2048, [1500, 900], 256),              # 512 workgroups: in-kernel hand-over without early loads
     (3, 32, 32, 1024, [1024, 1, 300], 128),           # 768 workgroups, most of them past the sequences' ends
     (1, 16, 16, 4096, [700], 256),                    # 256 workgroups (early loads), a cache six times the sequence
+    (2, 4, 4, 3000, [3000, 1700], 1152),              # a chunk length that is no power of two (capacity 2048)
+    (1, 4, 4, 1000, [1000], 80),                      # ... of 80 keys (capacity 128): 13 chunks
+    (2, 2, 2, 9000, [9000, 4100], 3008),              # ... of 3008 keys (capacity 4096)
 ]
 
 
@@ -58,7 +61,7 @@ def test_unified_and_sync_match_oracle(oracle, H, B, Hq, Hkv, Smax, lens, chunk)
     assert np.abs(got - got_sync).max() <= 1e-3
 
 
-@pytest.mark.parametrize("chunk", [64, 256, 1024])
+@pytest.mark.parametrize("chunk", [64, 256, 1024, 208])
 def test_partial_sums_match_eq4(oracle, H, chunk):
     case = synth.make_case(B=2, Hq=2, Hkv=2, D=128, Smax=1300, seed=200 + chunk, seq_lens=[1300, 515],
                            poison_padding=True)

@@ -35,7 +35,9 @@
  *   (null pointer, unsupported shape, bad bounds, workspace too small) are
  *   reported before anything is enqueued.  A failed launch returns FD_ERR_HIP.
  * Threads.  Calls are re-entrant as long as they use distinct workspaces.
- * Supported shapes.  head_dim == 128; chunk in {64, 128, 256, 512, 1024, 2048, 4096};
+ * Supported shapes.  head_dim == 128; chunk a multiple of 16 from 64 to 4096 keys (the
+ *   kernels are built for the powers of two in that range and run a chunk on the smallest
+ *   that holds it);
  *   n_q_heads a multiple of n_kv_heads; batch*n_q_heads*ceil(max_seq/chunk)
  *   < 2^31.
  */
@@ -86,10 +88,16 @@ typedef struct { void *ptr; size_t bytes; } fd_workspace;
 size_t fd_workspace_bytes(const fd_shape *shape);
 
 /* A chunk size (keys per partial vector, Section 3's split of the sequence axis)
- * suited to this shape on MI355X, one of 64 ... 1024 (up to 4096 for grouped heads); shape->chunk is
- * ignored.  0 if the rest of the shape is invalid or unsupported.  The paper leaves
- * the split size open; any supported value gives the same result up to rounding.
- * Pure host function.                                                          */
+ * suited to this shape on MI355X: a multiple of 16 from 64 to 2048 keys (to 4096 for
+ * grouped heads), chosen so that the workgroups -- one per (row or head group, chunk)
+ * -- cover the chip's 256 compute units in whole rounds; max_seq is cut into equal
+ * chunks, so the value is a power of two only where max_seq divides that way.
+ * shape->chunk is ignored.  0 if the rest of the shape is invalid or unsupported.
+ * It sees max_seq, not the lengths: a caller whose cache is much longer than its
+ * sequences gets a better value from a copy of the shape with max_seq set to the
+ * longest current length (any chunk is valid with any max_seq; the workspace size
+ * depends on both).  The paper leaves the split size open; any supported value gives
+ * the same result up to rounding.  Pure host function.                          */
 int32_t fd_pick_chunk(const fd_shape *shape);
 
 /*
@@ -171,7 +179,9 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
  *   block_table    [batch, max_seq / page_size] int32 (device): token t of sequence b
  *                  is row t % page_size of page block_table[b][t / page_size].
  * shape->max_seq is the logical capacity per sequence, a multiple of page_size;
- * page_size is a power of two >= 16 with shape->chunk <= 64 * page_size.  Only the
+ * page_size is a power of two >= 16 and a chunk touches at most 64 pages: chunk <=
+ * 64 * page_size when one of chunk and page_size divides the other, else chunk +
+ * page_size - 16 <= 64 * page_size (such a chunk may start inside a page).  Only the
  * entries of pages that hold a valid token (t < seq_lens[b]) are followed; the
  * others may hold anything (they are clamped into [0, n_pages) and what they bring
  * in is never used); an entry of a page in use that is out of range is the

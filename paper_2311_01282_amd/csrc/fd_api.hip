@@ -95,6 +95,7 @@ fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const v
     p->Smax = sh->max_seq; p->C = sh->chunk; p->nc = (int)L.nc; p->rows = (int)L.rows;
     p->scale = sh->scale; p->phi = 0.f; p->lo = 0.f; p->hi = 0.f;
     p->elect = 0;
+    p->chunk_major = 0;
     p->k_new = p->v_new = nullptr;
     p->k_store = p->v_store = nullptr;
     p->block_table = nullptr;

@@ -96,10 +96,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
 
     // All chunks of a KV-head group go to the same XCD (see decode_fused_kernel).
     const int groups = p.B * p.Hkv;
-    // chunk-major, so that chunks past the end of the sequences come last (see decode_fused_kernel)
+    // chunk-major in a launch of up to 1024 workgroups, so that chunks past the end of the
+    // sequences come last; row-major beyond (see decode_fused_kernel)
     const int groups8 = (groups + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int c = j / groups8, gi = (blockIdx.x & 7) + 8 * (j - c * groups8);
+    const int c = p.chunk_major ? j / groups8 : j % p.nc;
+    const int gi = (blockIdx.x & 7) + 8 * (p.chunk_major ? j - c * groups8 : j / p.nc);
     if (gi >= groups) return;
     const int b = gi / p.Hkv;
     const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group
@@ -378,11 +380,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
 }
 
 template <int C> struct GqaLauncher {
-    static hipError_t run(const Problem &p, hipStream_t s)
+    static hipError_t run(const Problem &p0, hipStream_t s)
     {
-        const long long groups = (long long)p.B * p.Hkv;
-        const unsigned grid = (unsigned)(8ll * ((groups + 7) / 8) * p.nc);
+        const long long groups = (long long)p0.B * p0.Hkv;
+        const unsigned grid = (unsigned)(8ll * ((groups + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
+        Problem p = p0;
+        p.chunk_major = grid <= 1024u;
         // 4 wavefronts per workgroup.  (8 were measured for launches of at most one workgroup per
         // compute unit: within 2 % either way at 256 workgroups, 12 % faster only for a lone
         // 4096-key chunk, which fd_pick_chunk never chooses.)

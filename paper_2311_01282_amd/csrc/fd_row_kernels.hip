@@ -44,15 +44,21 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     // go to the same XCD (row % 8), so the row's counters and partial results stay
     // in one L2 instead of bouncing between eight.  Placement only affects speed:
     // every hand-over below is device-coherent wherever the workgroups land.
-    // Order within that: chunk-major -- chunk 0 of every row, then chunk 1, ... -- so that the
-    // chunks past the end of the sequences (the launch covers max_seq) are dispatched last and
-    // leave at once, instead of taking a compute unit's first slot while another unit gets two
-    // full chunks.  (Against row-major, measured: 32.5 -> 25.8 us for 8192 keys in a cache of
-    // 8208, 107 -> 89 us for the grouped kernel on 32 sequences of 4096 in a cache of 8192,
-    // 4 % faster on large uniform batches, 2 % slower on the ragged batch of 16.)
+    // Order within that (p.chunk_major, chosen at launch):
+    //   a launch of up to 1024 workgroups goes chunk-major -- chunk 0 of every row, then chunk
+    //   1, ... -- so that the chunks past the end of the sequences (the launch covers max_seq)
+    //   are dispatched last and leave at once, instead of taking a compute unit's first slot
+    //   while another unit gets two full chunks (measured against row-major: 32.5 -> 25.8 us
+    //   for 8192 keys in a cache of 8208, 33.5 -> 29 us in a cache of 16384, 107 -> 89 us for
+    //   the grouped kernel on 32 sequences of 4096 keys in a cache of 8192);
+    //   a larger launch goes row-major: the dispatcher balances it as it goes, and the
+    //   workgroups in flight then cover whole rows -- every bit of the address below the row
+    //   stride -- where chunk-major confines a round of the chip to a slice of every row
+    //   (rows of a power-of-two stride: 8-10 % slower; the ragged batch of 16: 2 %).
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int c = j / groups8, row = (blockIdx.x & 7) + 8 * (j - c * groups8);
+    const int c = p.chunk_major ? j / groups8 : j % p.nc;
+    const int row = (blockIdx.x & 7) + 8 * (p.chunk_major ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     int S;
     const bool flagged = chunk_body<C, NW, UP, false, C, EARLY, PAGED>(p, row, c, lds, &S);
@@ -128,10 +134,12 @@ hipError_t dispatch_chunk(int C, Args... args)
 }
 
 template <int C> struct FusedLauncher {
-    static hipError_t run(const Problem &p, hipStream_t s)
+    static hipError_t run(const Problem &p0, hipStream_t s)
     {
-        const unsigned grid = (unsigned)(8ll * ((p.rows + 7) / 8) * p.nc);
+        const unsigned grid = (unsigned)(8ll * ((p0.rows + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
+        Problem p = p0;
+        p.chunk_major = grid <= 1024u;
         if (p.block_table)
             return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                            : launch(decode_fused_kernel<C, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);

@@ -167,10 +167,12 @@ size_t fd_workspace_bytes(const fd_shape *shape)
 //     workgroups.  Within 6 % of the best chunk on every shape of the sweep.
 //   grouped kernel: 1/G as many workgroups, each with four wavefronts' worth of loads in flight
 //     and a heavy tail (reduction over the group's heads); it is fastest with one workgroup
-//     per CU -- a single launch that finishes its rows itself -- so: the longest chunk, up to
-//     4096 keys, that still gives 256 workgroups and fills its last round of the chip
-//     (B x 64/8 heads x 4096 keys: 26.5 us at 1024 keys against 31.0 at 256 for B = 8; 84.5 at
-//     4096 against 89.8 at 1024 for B = 32).
+//     per CU -- a single launch that finishes its rows itself -- so: the fewest chunks, of up to
+//     4096 keys, that still give 256 workgroups and fill their last round of the chip
+//     (B x 64/8 heads x 4096 keys: 25.2 us at 1024 keys against 29.2 at 256 for B = 8; 80.8 at
+//     4096 against 87.6 at 1024 for B = 32).
+//   Both: max_seq is cut into equal chunks (a multiple of 16 keys, a power of two only where
+//     max_seq divides that way) so that launches of a few rounds of the chip fill their last one.
 int32_t fd_pick_chunk(const fd_shape *shape)
 {
     if (!shape) return 0;

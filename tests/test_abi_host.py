@@ -176,7 +176,9 @@ def test_pick_chunk_fills_the_chip_when_the_shape_allows_it(fdattn):
     # the shapes the sweeps were fitted on keep their power-of-two picks; lengths between them get equal chunks
     for shape, want in (((1, 32, 32, 8192), 1024), ((32, 64, 8, 4096), 4096), ((16, 64, 8, 4096), 2048), ((8, 64, 8, 4096), 1024),
                         ((16, 32, 32, 4096), 512), ((4, 32, 32, 32768), 1024), ((1, 32, 32, 9216), 1152), ((1, 32, 32, 12288), 1536),
-                        ((8, 64, 8, 5000), 1264), ((32, 64, 8, 4112), 2064)):
+                        ((8, 64, 8, 5000), 1264), ((32, 64, 8, 4112), 2064),
+                        # one round of the chip that is 90 % full beats two rounds when it needs at most 2/3 of the chunks
+                        ((5, 64, 8, 3000), 512), ((30, 64, 8, 4096), 4096), ((1, 64, 8, 32768), 1024)):
         assert fdattn.fd_pick_chunk(fdattn.make_shape(*shape[:3], 128, shape[3], 0, 0.1)) == want, shape
     # invalid shapes give 0
     assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0

@@ -206,8 +206,11 @@ def main():
             self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
             fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, stream)
             gqa = entry == "fd_decode_attn_gqa"
-            wgs = B * (Hkv if gqa else Hq) * (-(-Smax // chunk))
-            self.single_launch = wgs <= (256 if gqa else 1024) and entry in ("fd_decode_attn", "fd_decode_attn_gqa")
+            nc = -(-Smax // chunk)
+            wgs = B * (Hkv if gqa else Hq) * nc
+            # the library's own rule: the grouped kernel finishes its rows itself up to 256 workgroups and 8 chunks
+            # per row, the per-row kernel up to 1024 workgroups; beyond, the row epilogue is a launch of its own
+            self.single_launch = ((wgs <= 256 and nc <= 8) if gqa else wgs <= 1024) and entry in ("fd_decode_attn", "fd_decode_attn_gqa")
 
         def step(self, i):
             l = i % layers

@@ -116,14 +116,24 @@ fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
 // round trips at its end (results performed, arrival counter); a second launch costs
 // about 3 us once.  Small grids are latency-bound, so they fuse; large grids keep
 // their workgroups streaming and pay the launch.  FD_ELECT=0/1 overrides (tuning).
-inline int elect_in_kernel(long long workgroups, long long limit = 1024)
+inline int elect_in_kernel(long long workgroups, long long limit = 1024, bool and_also = true)
 {
     static const int forced = [] {
         const char *e = std::getenv("FD_ELECT");
         return e ? (e[0] == '0' ? 0 : 1) : -1;
     }();
     if (forced >= 0) return forced;
-    return workgroups <= limit;
+    return workgroups <= limit && and_also;
+}
+
+// The grouped kernel: its elected workgroup finishes the G rows of its head group by itself,
+// walking each row's chunks in order, which is the cheaper way up to 8 chunks per row and 256
+// workgroups; beyond either the second launch (one workgroup per row, 8 chunk slices in
+// parallel) wins: whole call, one launch / two, 64 query on 8 KV heads -- 25.7 / 26.4 us at 4
+// chunks per row, 17.4 / 17.2 at 8, 18.9 / 17.7 at 16, 18.0 / 15.3 at 24, 30.3 / 27.2 at 32.
+inline int elect_grouped(const fd::Problem &p)
+{
+    return elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256, p.nc <= 8);
 }
 
 #define FD_TRY(expr) do { if ((expr) != hipSuccess) return FD_ERR_HIP; } while (0)
@@ -315,7 +325,7 @@ fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k
     if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     // the grouped kernel holds fewer workgroups per CU, so the election hurts it sooner
-    p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
+    p.elect = elect_grouped(p);
     FD_TRY(fd::launch_decode_fused_gqa(p, s));
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;
@@ -339,7 +349,7 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
     p.v_store = static_cast<uint16_t *>(v_cache);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (p.G >= 2 && p.G <= 16) {
-        p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
+        p.elect = elect_grouped(p);
         FD_TRY(fd::launch_decode_fused_gqa(p, s));
     } else {
         p.elect = elect_in_kernel((long long)p.rows * p.nc);
@@ -371,7 +381,7 @@ static fd_status set_paged(fd::Problem *p, const fd_shape *shape, const int32_t 
 static fd_status run_fused(fd::Problem &p, hipStream_t s)
 {
     if (p.G >= 2 && p.G <= 16) {
-        p.elect = elect_in_kernel((long long)p.B * p.Hkv * p.nc, 256);
+        p.elect = elect_grouped(p);
         FD_TRY(fd::launch_decode_fused_gqa(p, s));
     } else {
         p.elect = elect_in_kernel((long long)p.rows * p.nc);

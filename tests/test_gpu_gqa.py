@@ -141,3 +141,22 @@ def test_gqa_single_chunk_sequences_publish_partials_and_recompute(oracle, H):
     keep = ~ocf.astype(bool)
     np.testing.assert_allclose(den[keep], oden[keep], rtol=2e-5, atol=0)
     assert (np.abs(num - onum)[keep] <= num_bound(case, oden)[keep][..., None]).all()
+
+
+@pytest.mark.parametrize("phi", [40.0, -15.0])
+def test_gqa_weights_at_both_ends_of_the_admissible_range(oracle, H, phi):
+    """Every weight e^{x - phi} near e^-40 (phi = 40) or near e^+15 (phi = -15): inside the bounds, so
+    nothing is flagged, and far outside what fp16 could hold -- the matrix-core operands (bf16 hi + lo)
+    must carry them; one key per sequence dominates its row as well."""
+    case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=1500, seed=440, seq_lens=[1500, 700], poison_padding=True)
+    synth.plant_keys(case, 2, 4.5, seed=441, allow_shared_kv=True)       # logit about 4.5: inside the bounds for both phi
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], phi, LO, HI, 512)
+    assert margin.min() > 1e-2 and not orf.any()
+    dc = H.DeviceCase(case, chunk=512)
+    got = dc.run("fd_decode_attn_gqa", phi=phi)
+    H.assert_close(got, want, "gqa, phi %g" % phi)
+    cf, rf, n, rows = dc.flags()
+    assert not cf.any() and not rf.any() and n == 0
+    # and through the per-row kernel, whose arithmetic is fp32 throughout
+    assert np.abs(got - dc.run("fd_decode_attn", phi=phi)).max() <= 1e-3

@@ -158,3 +158,25 @@ def test_invariance_to_phi_and_chunk(oracle, H):
             ref = got if ref is None else ref
             assert np.abs(got - ref).max() <= 2.5e-4      # <= a couple of fp16 ulps at |out| < 0.25
     H.assert_close(ref, exact(oracle, case), "invariance")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Smax,entry", [
+    (1, 32, 32, 9216, "fd_decode_attn"),          # 8 equal chunks of 1152 keys: 256 workgroups
+    (2, 32, 32, 5000, "fd_decode_attn"),          # 4 x 1264
+    (8, 64, 8, 5000, "fd_decode_attn_gqa"),       # grouped: 4 x 1264 keys, 256 workgroups
+    (5, 40, 8, 4096, "fd_decode_attn_gqa"),       # grouped, 5 heads per group: 6 x 688 keys, one round of 240 workgroups
+])
+def test_the_picked_chunk_on_lengths_that_do_not_divide(oracle, H, B, Hq, Hkv, Smax, entry):
+    """fd_pick_chunk's equal chunks (no power of two) end to end: output and flags against the oracle."""
+    from paper_2311_01282_amd import fdattn
+    case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=300 + Smax + B, poison_padding=True)
+    chunk = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, case["scale"]))
+    assert chunk % 16 == 0 and chunk & (chunk - 1) != 0
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk, nthreads=8)
+    dc = H.DeviceCase(case, chunk=chunk)
+    got = dc.run(entry)
+    H.assert_close(got, want, "%s, picked chunk %d" % (entry, chunk))
+    cf, rf, n, rows = dc.flags()
+    if margin.min() > 1e-2:
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)

@@ -181,7 +181,9 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
  * shape->max_seq is the logical capacity per sequence, a multiple of page_size;
  * page_size is a power of two >= 16 and a chunk touches at most 64 pages: chunk <=
  * 64 * page_size when one of chunk and page_size divides the other, else chunk +
- * page_size - 16 <= 64 * page_size (such a chunk may start inside a page).  Only the
+ * page_size - 16 <= 64 * page_size (such a chunk may start inside a page); fd_pick_chunk
+ * knows nothing of pages, so with small pages use the smaller of its value and
+ * 64 * page_size.  Only the
  * entries of pages that hold a valid token (t < seq_lens[b]) are followed; the
  * others may hold anything (they are clamped into [0, n_pages) and what they bring
  * in is never used); an entry of a page in use that is out of range is the

@@ -10,15 +10,19 @@
 //   weights  P = e^{s S^T - phi} in fp32, in place in the accumulator layout
 //            (lane (head, g) holds keys g, 4+g, 8+g, 12+g of the block) -- Eq. 4, no maximum.
 //            fp16 cannot hold e^{x-phi} over the admissible range of x - phi and bf16 has
-//            8 significant bits, so P goes to the matrix cores as bf16 hi + lo (16 bits),
-//            and V, whose fp16 values have 11, as bf16 hi + lo too (exact):
+//            8 significant bits, so P goes to the matrix cores as three bf16 pieces (hi + mid
+//            + lo = all 24 bits of the fp32 weight), and V, whose fp16 values have 11, as bf16
+//            hi + lo (exact):
 //   P.V      out[head][d] += sum_key P[head][key] V[key][d]
-//            v_mfma_f32_16x16x16_bf16, three per tile (hi.hi + hi.lo + lo.hi; lo.lo is below
-//            2^-16 of the term): A = P, whose four weights per lane are exactly contraction
+//            v_mfma_f32_16x16x16_bf16, five per tile (hi.hi + hi.lo + mid.hi + mid.lo + lo.hi;
+//            lo.lo is below 2^-24 of the term, so the sum is as good as an fp32 product --
+//            with two pieces of P, 2^-17 of a term, an output element that cancels to
+//            near zero in a sequence of a dozen keys missed the 1e-2 relative tolerance):
+//            A = P, whose four weights per lane are exactly contraction
 //            indices 4g..4g+3 when index 4g + r stands for key 4r + g; B = V, where lane
 //            (n, g) loads the 16 bytes d = 8n..8n+7 of the same keys 4r + g (r = 0..3) and
 //            feeds element e of the four rows to accumulator tile e (d = 8n + e), so V needs
-//            no transpose: 24 instructions per 16-key block, an eighth of the matrix-pipe
+//            no transpose: 40 instructions per 16-key block, a fifth of the matrix-pipe
 //            time of the fp32 16x16x4 form, paid for with about 4 vector-ALU operations
 //            per V element for the split.
 //
@@ -204,8 +208,17 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
         }
         // P as the A operand of the 16x16x16 product: lane (head n, g) holds contraction indices
         // 4g .. 4g+3, which stand for keys g, 4+g, 8+g, 12+g -- its own four weights.
-        bf16x4 p_hi, p_lo;
-        split_bf16<false>(pw, p_hi, p_lo);
+        // Three bf16 pieces carry a weight's 24 bits: hi and mid by truncation, lo what is left.
+        bf16x4 p_hi, p_mid, p_lo, unused;
+        float rest[4];
+        split_bf16<true>(pw, p_hi, p_mid);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float top = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, pw[r]) & 0xffff0000u);
+            const float below = pw[r] - top;                                  // exact
+            rest[r] = below - __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, below) & 0xffff0000u);   // exact
+        }
+        split_bf16<false>(rest, p_lo, unused);       // rest has at most 8 significant bits: p_lo is exact, its own rest zero
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             // dword w of the four V rows: elements d = 8n + 2w (low halves) and 8n + 2w + 1 (high halves)
@@ -219,12 +232,17 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
             bf16x4 e_hi, e_lo, o_hi, o_lo;
             split_bf16<true>(even, e_hi, e_lo);
             split_bf16<true>(odd, o_hi, o_lo);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_hi, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_hi, acc[2 * w + 1], 0, 0, 0);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_lo, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_lo, acc[2 * w + 1], 0, 0, 0);
+            // smallest products first; (p_lo . V_lo is below 2^-24 of the term)
             acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, e_hi, acc[2 * w], 0, 0, 0);
             acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, o_hi, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, e_lo, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, o_lo, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, e_hi, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, o_hi, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_lo, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_lo, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_hi, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_hi, acc[2 * w + 1], 0, 0, 0);
         }
     };
     // This wavefront's blocks are wave, wave + NW, ...; nmine of them hold a valid key.

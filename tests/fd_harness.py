@@ -87,15 +87,15 @@ class DeviceCase:
                 self._view(den, 4 * self.rows * self.nc, np.float32, (B, Hq, self.nc)))
 
 
-def errors(got, want):
-    """(max abs error, max relative error with the REL_FLOOR denominator floor)"""
+def errors(got, want, rel_floor=REL_FLOOR):
+    """(max abs error, max relative error with the denominator floor)"""
     diff = np.abs(got - want)
-    return float(diff.max(initial=0.0)), float((diff / np.maximum(np.abs(want), REL_FLOOR)).max(initial=0.0))
+    return float(diff.max(initial=0.0)), float((diff / np.maximum(np.abs(want), rel_floor)).max(initial=0.0))
 
 
-def assert_close(got, want, what=""):
+def assert_close(got, want, what="", rel_floor=REL_FLOOR):
     assert np.isfinite(got).all(), "%s: non-finite output" % what
-    a, r = errors(got, want)
+    a, r = errors(got, want, rel_floor)
     assert a <= ABS_TOL and r <= REL_TOL, "%s: max-abs %.3e (tol %.0e), max-rel %.3e (tol %.0e)" % (
         what, a, ABS_TOL, r, REL_TOL)
     return a, r

@@ -20,6 +20,18 @@ def H():
     return fd_harness
 
 
+# The prompt-phase kernel feeds its weights to the matrix cores as bf16 hi + lo, both rounded to
+# nearest: 2^-18 of a term.  In a row of a handful of keys whose terms nearly cancel, that is up
+# to 2^-18 * max|v| = 1.7e-5 on an element near zero (a randomized sweep of short prompts found
+# 1.05e-5 on 8.8e-4), so the relative error is measured against max(|oracle|, 2e-3) here, where the
+# decode tests use 1e-3; the absolute bound (2e-3) and the relative one (1e-2) are the same.
+PREFILL_REL_FLOOR = 2e-3
+
+
+def close(H, got, want, what):
+    return H.assert_close(got, want, what, rel_floor=PREFILL_REL_FLOOR)
+
+
 def draw(B, Hq, Hkv, Smax, lens, seed, poison=True):
     rng = np.random.default_rng(seed)
     D = 128
@@ -80,7 +92,7 @@ def test_every_row_matches_oracle(H, B, Hq, Hkv, Smax, lens):
     want, flag, margin = pf.prefill_rows(q, k, v, sl, scale, rows, phi=synth.PHI, lo=LO, hi=HI, nthreads=8)
     assert margin.min() > 1e-2 and not flag.any()
     got, tf = run_gpu(q, k, v, sl, scale)
-    H.assert_close(got.reshape(-1, 128), want, "prefill %s" % ((B, Hq, Hkv, Smax),))
+    close(H, got.reshape(-1, 128), want, "prefill %s" % ((B, Hq, Hkv, Smax),))
     assert not tf.any()
     for b in range(B):                       # rows beyond the prompt are zero
         assert not got[b, :, sl[b]:].any()
@@ -97,7 +109,7 @@ def test_long_prompt_sampled_rows(H):
     want, flag, margin = pf.prefill_rows(q, k, v, sl, scale, rows, phi=synth.PHI, lo=LO, hi=HI, nthreads=16)
     assert margin.min() > 1e-2 and not flag.any()
     got, tf = run_gpu(q, k, v, sl, scale)
-    H.assert_close(got[rows[:, 0], rows[:, 1], rows[:, 2]], want, "prefill 2048")
+    close(H, got[rows[:, 0], rows[:, 1], rows[:, 2]], want, "prefill 2048")
     assert not tf.any() and np.isfinite(got).all()
     assert not got[1, :, 1500:].any()
 
@@ -122,7 +134,7 @@ def test_flagged_tiles_are_recomputed(H):
     assert want_tf[0, 2].tolist() == [0, 0, 1, 1, 1] and want_tf.sum() == 3
     got, tf = run_gpu(q, k, v, sl, scale)
     assert np.array_equal(tf, want_tf)
-    H.assert_close(got.reshape(-1, 128), want, "prefill with recomputation")
+    close(H, got.reshape(-1, 128), want, "prefill with recomputation")
 
 
 def test_nan_logit_flags_its_tiles(H):
@@ -141,7 +153,7 @@ def test_nan_logit_flags_its_tiles(H):
     got = got.reshape(-1, 128)
     clean = np.isfinite(want).all(axis=1)
     assert clean.sum() == Smax + 70 + (Smax - 230)      # head 0, head 1 before the key, rows past the prompt
-    H.assert_close(got[clean], want[clean], "prefill rows that do not see the NaN key")
+    close(H, got[clean], want[clean], "prefill rows that do not see the NaN key")
     assert np.isnan(got[~clean]).all()
 
 
@@ -156,7 +168,7 @@ def test_lower_bound_flags_too(H):
     assert margin.min() > 1e-2
     got, tf = run_gpu(q, k, v, sl, scale, phi=100.0)
     assert np.array_equal(tf, tile_flags_from_rows(rows, flag, B, Hq, Smax)) and tf.sum() == 2 * 3
-    H.assert_close(got.reshape(-1, 128), want, "prefill, all tiles recomputed")
+    close(H, got.reshape(-1, 128), want, "prefill, all tiles recomputed")
 
 
 def test_prefill_can_be_captured_and_replayed(H):
@@ -207,3 +219,19 @@ def test_prefill_rejects_bad_arguments():
         with pytest.raises(fdattn.FdError) as e:
             fdattn.fd_prefill_attn(*args)
         assert e.value.status == code
+
+
+def test_short_prompts_sweep(H):
+    """Rows of a handful of keys are where the bf16 hi + lo weights show (see PREFILL_REL_FLOOR):
+    forty seeded short prompts, every row against the oracle."""
+    scale = float(np.float32(1.0 / np.sqrt(128.0)))
+    for seed in range(100, 140):
+        rng = np.random.default_rng(seed)
+        B = int(rng.integers(1, 4)); Hkv = int(rng.choice([1, 2, 4])); Hq = Hkv * int(rng.choice([1, 2, 4]))
+        Smax = int(rng.integers(16, 200))
+        lens = [int(x) for x in rng.integers(1, Smax + 1, size=B)]
+        q, k, v, sl = draw(B, Hq, Hkv, Smax, lens, seed=90000 + seed)
+        rows = pf.all_rows(B, Hq, Smax)
+        want, flag, margin = pf.prefill_rows(q, k, v, sl, scale, rows, phi=synth.PHI, lo=LO, hi=HI, nthreads=8)
+        got, tf = run_gpu(q, k, v, sl, scale)
+        close(H, got.reshape(-1, 128), want, "short prompts, seed %d %s" % (seed, (B, Hq, Hkv, Smax, lens)))

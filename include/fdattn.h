@@ -123,7 +123,8 @@ fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream
  *      sums of Eq. 4, flagged rows by the synchronized update of Eq. 2 over all
  *      partial results, each rescaled from its own reference (phi, or the chunk
  *      maximum) to the row maximum of those references.  For grids of more than
- *      1024 workgroups (256 for fd_decode_attn_gqa) step 3 runs as a second, tiny
+ *      1024 workgroups (fd_decode_attn_gqa: more than 256 workgroups, or more than 8
+ *      chunks per row) step 3 runs as a second, tiny
  *      launch instead (one workgroup per row, no counters): large grids are
  *      throughput-bound and the election's two memory round trips per workgroup
  *      cost more than a launch.
@@ -143,7 +144,9 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
  * n_q_heads / n_kv_heads query heads that share one KV head are processed
  * together so each K and V element is read from memory once per group.
  * Requires 2 <= n_q_heads / n_kv_heads <= 16.  (Grouping is not in the paper;
- * per query head the arithmetic is Eq. 4 unchanged.)  Flags are per query head.
+ * per query head the arithmetic is Eq. 4 unchanged: the weights e^{x-phi} are formed
+ * in fp32 and enter the second product with all 24 bits, as three bf16 pieces on the
+ * matrix cores.)  Flags are per query head.
  * Requires fd_workspace_init.
  */
 fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,

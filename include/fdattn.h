@@ -181,7 +181,11 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
  *   k_pool, v_pool [n_pages, n_kv_heads, page_size, head_dim] fp16
  *   block_table    [batch, max_seq / page_size] int32 (device): token t of sequence b
  *                  is row t % page_size of page block_table[b][t / page_size].
- * shape->max_seq is the logical capacity per sequence, a multiple of page_size;
+ * shape->max_seq is the logical capacity per sequence, a multiple of page_size -- here only
+ * the width of block_table, so a caller that rebuilds its table every step can (and should)
+ * pass the longest current length rounded up to a page: the launch covers max_seq, and
+ * chunks past a sequence's end cost a workgroup each (they leave at once, but a cache sized
+ * for 32768 tokens holding 2000 would launch sixteen times the workgroups it needs);
  * page_size is a power of two >= 16 and a chunk touches at most 64 pages: chunk <=
  * 64 * page_size when one of chunk and page_size divides the other, else chunk +
  * page_size - 16 <= 64 * page_size (such a chunk may start inside a page); fd_pick_chunk

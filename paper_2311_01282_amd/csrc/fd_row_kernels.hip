@@ -44,7 +44,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     // go to the same XCD (row % 8), so the row's counters and partial results stay
     // in one L2 instead of bouncing between eight.  Placement only affects speed:
     // every hand-over below is device-coherent wherever the workgroups land.
-    // Order within that (p.chunk_major, chosen at launch):
+    // Order within that, chosen at launch:
     //   a launch of up to 1024 workgroups goes chunk-major -- chunk 0 of every row, then chunk
     //   1, ... -- so that the chunks past the end of the sequences (the launch covers max_seq)
     //   are dispatched last and leave at once, instead of taking a compute unit's first slot
@@ -55,10 +55,14 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     //   workgroups in flight then cover whole rows -- every bit of the address below the row
     //   stride -- where chunk-major confines a round of the chip to a slice of every row
     //   (rows of a power-of-two stride: 8-10 % slower; the ragged batch of 16: 2 %).
+    // (For this kernel the two limits coincide -- in-kernel hand-over and chunk-major order both
+    // end at 1024 workgroups -- so the order is a compile-time choice: one division, not two.
+    // Multiply-shift quotients from precomputed reciprocals and a two-dimensional launch were
+    // both measured slower than this: c1 24.0 us against 23.75.)
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int c = p.chunk_major ? j / groups8 : j % p.nc;
-    const int row = (blockIdx.x & 7) + 8 * (p.chunk_major ? j - c * groups8 : j / p.nc);
+    const int c = ELECT ? j / groups8 : j % p.nc;
+    const int row = (blockIdx.x & 7) + 8 * (ELECT ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     int S;
     const bool flagged = chunk_body<C, NW, UP, false, C, EARLY, PAGED>(p, row, c, lds, &S);
@@ -139,7 +143,7 @@ template <int C> struct FusedLauncher {
         const unsigned grid = (unsigned)(8ll * ((p0.rows + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
         Problem p = p0;
-        p.chunk_major = grid <= 1024u;
+        p.chunk_major = p.elect;                   // what the kernel compiles in (the grouped kernel reads the flag)
         if (p.block_table)
             return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                            : launch(decode_fused_kernel<C, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);

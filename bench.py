@@ -311,7 +311,8 @@ def main():
         if nbytes_each % 65536 == 0 and valid_keys == B * Smax:
             # plain streaming read of the same K and V buffers: the measured ceiling
             sink = torch.zeros(1, dtype=torch.int32, device=dev)
-            p_sec = events(lambda i: fdattn.fd_probe_stream_read(ks[i % layers].data_ptr(), vs[i % layers].data_ptr(),
+            from paper_2311_01282_amd import fdprobe
+            p_sec = events(lambda i: fdprobe.fd_probe_stream_read(ks[i % layers].data_ptr(), vs[i % layers].data_ptr(),
                                                                   nbytes_each, sink.data_ptr(), stream),
                            short, 10)
             roofline["stream_read_ceiling_gbs"] = round(2 * nbytes_each / p_sec / 1e9, 1)

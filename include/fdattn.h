@@ -6,22 +6,32 @@
  * cache; the sequence axis is cut into chunks ("partial vectors"); every chunk
  * accumulates e^{x - phi} and e^{x - phi} v against ONE unified scaling factor
  * phi, so chunk results simply add (Eq. 3, Eq. 4); a chunk whose logits leave
- * a < x - phi < b raises a flag and the whole row is recomputed with the
- * synchronized partial softmax of Eq. 2 (Section 3, "Recomputation").
+ * a < x - phi < b raises a flag and its row is produced by the synchronized
+ * partial softmax of Eq. 2 instead (Section 3, "Recomputation").  How much of a
+ * flagged row is re-read differs by entry point: fd_decode_attn_multikernel
+ * recomputes every chunk of the row, as the paper's text has it; fd_decode_attn
+ * and its variants recompute only the chunks that left the bounds and merge all
+ * of the row's partial results by Eq. 2 (see the description of each call).
  *
  * Conventions common to every call
  * --------------------------------
  * Memory.  Every data pointer is DEVICE memory allocated and owned by the
  *   caller (hipMalloc or a framework tensor).  The library allocates nothing,
- *   frees nothing and keeps no state between calls.  Inputs are never written.
+ *   frees nothing and keeps no state of its own between calls (no globals, no
+ *   environment variables); what fd_decode_attn and its variants carry from one
+ *   call to the next lives in the caller's workspace (see fd_workspace_init).
+ *   Inputs are never written.
  * Layouts (all contiguous, row-major, IEEE binary16 unless noted):
  *   q        [batch, n_q_heads, head_dim]
  *   k_cache  [batch, n_kv_heads, max_seq, head_dim]
  *   v_cache  [batch, n_kv_heads, max_seq, head_dim]
  *   seq_lens [batch] int32 -- valid keys per sequence; values are clamped to
- *            [0, max_seq]; cache positions >= the valid length are padding and
- *            are never read.  A sequence of length 0 produces a zero row and
- *            raises no flag.
+ *            [0, max_seq]; cache positions >= the valid length are padding:
+ *            they may hold anything (NaN included) and never enter a result.
+ *            They may still be LOADED, within the allocated [.., max_seq, ..]
+ *            extent of the caches only (small launches request a chunk's first
+ *            block before the length has arrived and discard what lies beyond
+ *            it).  A sequence of length 0 produces a zero row and raises no flag.
  *   out      [batch, n_q_heads, head_dim]
  *   All pointers must be 16-byte aligned.
  *   Query head hq reads KV head hq / (n_q_heads / n_kv_heads).
@@ -78,9 +88,13 @@ typedef struct { float lo, hi; } fd_bounds;
 
 /* Caller-owned device scratch of at least fd_workspace_bytes(shape) bytes,
  * 256-byte aligned.  After a call it holds that call's partial results and
- * flags (see fd_get_flags, fd_get_partials).  fd_decode_attn and
- * fd_decode_attn_gqa need the workspace prepared once by fd_workspace_init; the
- * other calls accept arbitrary previous contents.                             */
+ * flags (see fd_get_flags, fd_get_partials).  fd_decode_attn and its variants
+ * (_gqa, _append, _paged, _paged_append) need the workspace prepared once by
+ * fd_workspace_init; the other calls accept arbitrary previous contents.
+ * Layout: the data sections start at ptr and grow with the number of
+ * (row, chunk) slots; the arrival counters of fd_workspace_init END at the last
+ * 256-byte boundary inside [ptr, ptr + bytes).  Describe one allocation by the
+ * same (ptr, bytes) pair in every call.                                       */
 typedef struct { void *ptr; size_t bytes; } fd_workspace;
 
 /* Bytes of workspace the calls below need for this shape; 0 if the shape is
@@ -101,12 +115,21 @@ size_t fd_workspace_bytes(const fd_shape *shape);
 int32_t fd_pick_chunk(const fd_shape *shape);
 
 /*
- * Prepare a workspace for fd_decode_attn / fd_decode_attn_gqa: zeroes the
- * per-row arrival tickets (one int32 per row) those calls use to elect the
- * workgroup that finishes a row.  Enqueue once after allocating the workspace
- * (or after changing the shape it is used with); every completed call leaves
- * the tickets zero again, so steady-state calls need no re-initialisation.  A
- * call that was aborted mid-flight (device reset, failed launch) needs a new one.
+ * Prepare a workspace for fd_decode_attn and its variants: zeroes the arrival
+ * counters (one int32 per (row, chunk) slot) by which the workgroups of those
+ * calls elect the one that finishes a row.  It clears the counters of EVERY shape
+ * that fits into ws.bytes, not just of `shape` (which only has to be valid and to
+ * fit): enqueue it once after allocating the workspace; after that the shape --
+ * batch, heads, max_seq, chunk -- may change from call to call, as it does for a
+ * caller that passes the longest current length as max_seq or re-picks the chunk
+ * every step, as long as each shape's fd_workspace_bytes fits and (ptr, bytes)
+ * stay the same.  Every completed call leaves the counters zero again.
+ * A call that did not complete (device reset, a launch that failed half-way
+ * through a call, a kernel killed mid-flight) may leave counters non-zero: a
+ * later call then elects nobody for the rows concerned, i.e. their `out` rows and
+ * row flags are NOT written (nothing else goes wrong, and no error is reported).
+ * After any such event enqueue fd_workspace_init again before reusing the
+ * workspace.
  */
 fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream);
 
@@ -134,6 +157,8 @@ fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream
  * recomputes every chunk of a flagged row instead; both give the same result up
  * to fp32 rounding.  Works for any head grouping (each query head is a row).
  * Requires fd_workspace_init.  Fills chunk_flags and row_flags.
+ * Which of the two launch forms runs depends on the shape alone (the numbers
+ * above); no environment variable or other hidden switch takes part.
  */
 fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cache,
                          const void *v_cache, const int32_t *seq_lens, float phi,
@@ -381,16 +406,6 @@ fd_status fd_prefill_attn(const fd_shape *shape, const void *q, const void *k_ca
 /* Device pointer into `ws`: tile_flags [batch, n_q_heads, ceil(max_seq / 64)], 1 where
  * the guard fired for a logit of those 64 queries (their 128-query tile was recomputed). */
 fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uint8_t **tile_flags);
-
-/*
- * Measurement aid, not part of the method: enqueue a plain streaming read of two
- * device buffers of `bytes_each` bytes each (a multiple of 65536) with the same
- * launch geometry as the chunk kernel and no arithmetic.  `sink` is 4 bytes of
- * device memory (practically never written).  Timing this gives the read rate a
- * kernel of that shape can reach on the device at hand.
- */
-fd_status fd_probe_stream_read(const void *a, const void *b, size_t bytes_each,
-                               void *sink, void *stream);
 
 /* Static, human-readable name of a status code. */
 const char *fd_status_str(fd_status status);

@@ -15,7 +15,10 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfdattn.so")
 SOURCES = ["fd_api.hip", "fd_row_kernels.hip", "fd_reduce_kernels.hip", "fd_gqa_kernels.hip",
-           "fd_stats_kernels.hip", "fd_prefill_kernels.hip", "fd_probe_kernels.hip"]
+           "fd_stats_kernels.hip", "fd_prefill_kernels.hip"]
+# the benchmark's streaming-read probe: a library of its own, not part of libfdattn
+PROBE_LIB = os.path.join(HERE, "libfdprobe.so")
+PROBE_SOURCES = ["fd_probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed-fp32 VALU forms are kept out of the generated code on purpose
@@ -37,15 +40,20 @@ def _compile(src, extra):
     return obj
 
 
+def _link(lib, objs):
+    tmp = lib + ".tmp%d" % os.getpid()
+    subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+    os.replace(tmp, lib)
+
+
 def build(extra_flags=(), verbose=False):
     os.makedirs(BUILD, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES))
-    tmp = LIB + ".tmp%d" % os.getpid()
-    subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
-    os.replace(tmp, LIB)
+        objs = list(ex.map(lambda s: _compile(s, extra_flags), SOURCES + PROBE_SOURCES))
+    _link(LIB, objs[:len(SOURCES)])
+    _link(PROBE_LIB, objs[len(SOURCES):])
     if verbose:
-        print("built", LIB)
+        print("built", LIB, PROBE_LIB)
     return LIB
 
 

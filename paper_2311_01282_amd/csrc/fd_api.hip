@@ -4,7 +4,6 @@
 
 #include <cfloat>
 #include <cmath>
-#include <cstdlib>
 
 namespace {
 
@@ -12,9 +11,33 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t num, den, mloc, chunk_flags, meta, row_flags, list, count, ticket, total;
+    size_t num, den, mloc, chunk_flags, meta, row_flags, list, count, data_end, ticket_bytes, total;
     long long rows, nc;
 };
+
+// Bytes of the data sections (everything but the arrival counters) and of the arrival
+// counters for `slots` (row, chunk) pairs.  Both depend on the slot count alone and grow with
+// it -- the per-row arrays are sized by slots >= rows -- which is what lets one workspace
+// serve different shapes: data sections grow upwards from offset 0, the counters sit at the
+// END of the workspace, and for any two shapes that fit the same workspace the data of one
+// never reaches the counters of the other.
+inline size_t data_bytes(size_t slots, Layout *L = nullptr)
+{
+    Layout tmp;
+    if (!L) L = &tmp;
+    size_t off = 0;
+    L->num = off;          off = align_up(off + slots * fd::kHeadDim * sizeof(float));
+    L->den = off;          off = align_up(off + slots * sizeof(float));
+    L->mloc = off;         off = align_up(off + slots * sizeof(float));
+    L->chunk_flags = off;  off = align_up(off + slots);
+    L->meta = off;         off = align_up(off + slots * sizeof(fd::SlotMeta));
+    L->row_flags = off;    off = align_up(off + slots);
+    L->list = off;         off = align_up(off + slots * sizeof(int32_t));
+    L->count = off;        off = align_up(off + sizeof(int32_t));
+    L->data_end = off;
+    return off;
+}
+inline size_t ticket_bytes(size_t slots) { return align_up(slots * sizeof(int32_t)); }
 
 // FD_OK and a filled layout, or the reason the shape cannot be served.
 fd_status plan(const fd_shape *sh, Layout *L)
@@ -31,17 +54,9 @@ fd_status plan(const fd_shape *sh, Layout *L)
     const long long nc = ((long long)sh->max_seq + sh->chunk - 1) / sh->chunk;
     if (rows * nc >= (1ll << 31)) return FD_ERR_UNSUPPORTED;
     const size_t slots = (size_t)(rows * nc);
-    size_t off = 0;
-    L->num = off;          off = align_up(off + slots * fd::kHeadDim * sizeof(float));
-    L->den = off;          off = align_up(off + slots * sizeof(float));
-    L->mloc = off;         off = align_up(off + slots * sizeof(float));
-    L->chunk_flags = off;  off = align_up(off + slots);
-    L->meta = off;         off = align_up(off + slots * sizeof(fd::SlotMeta));
-    L->row_flags = off;    off = align_up(off + (size_t)rows);
-    L->list = off;         off = align_up(off + (size_t)rows * sizeof(int32_t));
-    L->count = off;        off = align_up(off + sizeof(int32_t));
-    L->ticket = off;       off = align_up(off + slots * sizeof(int32_t));
-    L->total = off;
+    data_bytes(slots, L);
+    L->ticket_bytes = ticket_bytes(slots);
+    L->total = L->data_end + L->ticket_bytes;
     L->rows = rows;
     L->nc = nc;
     return FD_OK;
@@ -51,6 +66,22 @@ fd_status check_ws(const Layout &L, fd_workspace ws)
 {
     if (!ws.ptr || ((uintptr_t)ws.ptr % kAlign) != 0 || ws.bytes < L.total) return FD_ERR_WORKSPACE;
     return FD_OK;
+}
+
+// End of the workspace as the counters see it: the last 256-byte boundary inside it.
+inline char *ws_end(fd_workspace ws) { return static_cast<char *>(ws.ptr) + ws.bytes / kAlign * kAlign; }
+
+// The arrival-counter region that fd_workspace_init clears: large enough for every shape
+// this workspace can hold (the largest slot count whose data and counters still fit).
+inline size_t max_ticket_bytes(size_t ws_bytes)
+{
+    size_t lo = 0, hi = (size_t)1 << 31;            // slots: lo fits, hi does not
+    if (data_bytes(0) + ticket_bytes(0) > ws_bytes) return 0;
+    while (hi - lo > 1) {
+        const size_t mid = lo + (hi - lo) / 2;
+        if (data_bytes(mid) + ticket_bytes(mid) <= ws_bytes) lo = mid; else hi = mid;
+    }
+    return ticket_bytes(lo);
 }
 
 fd::WsView view(const Layout &L, fd_workspace ws)
@@ -65,7 +96,7 @@ fd::WsView view(const Layout &L, fd_workspace ws)
     w.row_flags = reinterpret_cast<uint8_t *>(base + L.row_flags);
     w.list = reinterpret_cast<int32_t *>(base + L.list);
     w.count = reinterpret_cast<int32_t *>(base + L.count);
-    w.ticket = reinterpret_cast<int32_t *>(base + L.ticket);
+    w.ticket = reinterpret_cast<int32_t *>(ws_end(ws) - L.ticket_bytes);
     return w;
 }
 
@@ -115,14 +146,9 @@ fd_status set_guard(fd::Problem *p, float phi, fd_bounds b)
 // to a second, tiny launch.  Electing a finisher costs every workgroup two memory
 // round trips at its end (results performed, arrival counter); a second launch costs
 // about 3 us once.  Small grids are latency-bound, so they fuse; large grids keep
-// their workgroups streaming and pay the launch.  FD_ELECT=0/1 overrides (tuning).
+// their workgroups streaming and pay the launch.
 inline int elect_in_kernel(long long workgroups, long long limit = 1024, bool and_also = true)
 {
-    static const int forced = [] {
-        const char *e = std::getenv("FD_ELECT");
-        return e ? (e[0] == '0' ? 0 : 1) : -1;
-    }();
-    if (forced >= 0) return forced;
     return workgroups <= limit && and_also;
 }
 
@@ -191,7 +217,8 @@ int32_t fd_pick_chunk(const fd_shape *shape)
     Layout L;
     if (plan(&sh, &L) != FD_OK) return 0;
     static const int32_t sizes[] = {4096, 2048, 1024, 512, 256, 128, 64};
-    const bool grouped = sh.n_q_heads != sh.n_kv_heads;
+    const int group = sh.n_q_heads / sh.n_kv_heads;
+    const bool grouped = group >= 2 && group <= 16;   // the shapes that run on the grouped kernel
     const long long units = (long long)sh.batch * (grouped ? sh.n_kv_heads : sh.n_q_heads);
     auto workgroups = [&](int32_t c) { return units * (((long long)sh.max_seq + c - 1) / c); };
     auto largest_with = [&](long long want, int32_t shortest, int32_t longest) -> int32_t {
@@ -288,10 +315,15 @@ fd_status fd_decode_attn_gqa_partial(const fd_shape *shape, const void *q, const
 
 fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream)
 {
-    fd::Problem p;
-    fd_status st = make_ws_problem(shape, ws, &p);
+    Layout L;
+    fd_status st = plan(shape, &L);
     if (st != FD_OK) return st;
-    FD_TRY(fd::launch_clear_tickets(p, static_cast<hipStream_t>(stream)));
+    st = check_ws(L, ws);
+    if (st != FD_OK) return st;
+    // every counter any shape could use in this workspace, not just this shape's
+    const size_t bytes = max_ticket_bytes(ws.bytes);
+    FD_TRY(fd::launch_clear_tickets(reinterpret_cast<int32_t *>(ws_end(ws) - bytes), bytes / sizeof(int32_t),
+                                    static_cast<hipStream_t>(stream)));
     return FD_OK;
 }
 
@@ -649,16 +681,6 @@ fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uin
     if (st != FD_OK) return st;
     if (!ws.ptr || ((uintptr_t)ws.ptr % kAlign) != 0 || ws.bytes < P.total) return FD_ERR_WORKSPACE;
     if (tile_flags) *tile_flags = reinterpret_cast<const uint8_t *>(static_cast<char *>(ws.ptr) + P.flags);
-    return FD_OK;
-}
-
-fd_status fd_probe_stream_read(const void *a, const void *b, size_t bytes_each,
-                               void *sink, void *stream)
-{
-    if (!a || !b || !sink) return FD_ERR_NULL;
-    if (bytes_each % 65536 != 0 || misaligned(a) || misaligned(b)) return FD_ERR_SHAPE;
-    FD_TRY(fd::launch_stream_read(a, b, bytes_each, static_cast<unsigned *>(sink),
-                                  static_cast<hipStream_t>(stream)));
     return FD_OK;
 }
 

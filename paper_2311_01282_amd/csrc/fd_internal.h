@@ -36,10 +36,11 @@ struct WsView {
     float   *mloc;         // [rows, nc]       chunk maximum m (synchronized scheme only)
     uint8_t *chunk_flags;  // [rows, nc]
     SlotMeta *meta;        // [rows, nc]  (den, reference, flag) handed to the row epilogue
-    uint8_t *row_flags;    // [rows]
-    int32_t *list;         // [rows]  flagged rows, ascending
+    uint8_t *row_flags;    // [rows]  (room for rows * nc)
+    int32_t *list;         // [rows]  flagged rows, ascending (room for rows * nc)
     int32_t *count;        // [1]     number of flagged rows
-    int32_t *ticket;       // [rows, nc]  arrival counters (a small tree per row) of the fused kernels; zero between calls
+    int32_t *ticket;       // [rows, nc]  arrival counters (a small tree per row) of the fused kernels; zero between
+                           // calls; they end where the workspace ends, whatever the shape
 };
 
 struct Problem {
@@ -99,7 +100,7 @@ hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s);
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s);
 hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
 hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
-hipError_t launch_clear_tickets(const Problem &p, hipStream_t s);
+hipError_t launch_clear_tickets(int32_t *ticket, size_t n, hipStream_t s);
 hipError_t launch_row_epilogue(const Problem &p, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)
 hipError_t launch_decode_fused_gqa(const Problem &p, hipStream_t s);
@@ -117,7 +118,5 @@ struct PrefillProblem {
     float scale, phi, lo, hi;
 };
 hipError_t launch_prefill(const PrefillProblem &p, hipStream_t s);
-// fd_probe_kernels.hip : plain streaming read used as a measured bandwidth ceiling
-hipError_t launch_stream_read(const void *a, const void *b, size_t bytes_each, unsigned *sink, hipStream_t s);
 
 }  // namespace fd

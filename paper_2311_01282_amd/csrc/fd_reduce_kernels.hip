@@ -6,10 +6,9 @@
 namespace fd {
 namespace {
 
-__global__ __launch_bounds__(256) void clear_tickets_kernel(int32_t *ticket, int n)
+__global__ __launch_bounds__(256) void clear_tickets_kernel(int32_t *ticket, size_t n)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) ticket[i] = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) ticket[i] = 0;
 }
 
 // The row epilogue as a launch of its own (one workgroup per row), used when the
@@ -115,11 +114,11 @@ __global__ __launch_bounds__(kHeadDim) void combine_sync_kernel(const Problem p,
 
 }  // namespace
 
-hipError_t launch_clear_tickets(const Problem &p, hipStream_t s)
+hipError_t launch_clear_tickets(int32_t *ticket, size_t n, hipStream_t s)
 {
-    const int n = p.rows * p.nc;
     if (n == 0) return hipSuccess;
-    return launch(clear_tickets_kernel, dim3((n + 255) / 256), dim3(256), s, p.ws.ticket, n);
+    const size_t blocks = (n + 255) / 256;
+    return launch(clear_tickets_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), s, ticket, n);
 }
 
 hipError_t launch_row_epilogue(const Problem &p, hipStream_t s)

@@ -70,8 +70,6 @@ _lib.fd_workspace_init.restype = ctypes.c_int
 _lib.fd_workspace_init.argtypes = [_sp, Workspace, _vp]
 _lib.fd_list_flagged_rows.restype = ctypes.c_int
 _lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
-_lib.fd_probe_stream_read.restype = ctypes.c_int
-_lib.fd_probe_stream_read.argtypes = [_vp, _vp, ctypes.c_size_t, _vp, _vp]
 
 class Calibration(ctypes.Structure):
     _fields_ = [("apply", ctypes.c_int32), ("phi", ctypes.c_float), ("bounds", Bounds),
@@ -101,7 +99,7 @@ _lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
 
 EXPORTS = ("fd_decode_attn_paged", "fd_decode_attn_paged_append", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
-           "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials", "fd_probe_stream_read",
+           "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials",
            "fd_status_str")
 
 
@@ -179,10 +177,6 @@ def fd_get_partials(shape, ws_ptr, ws_bytes):
     _check(_lib.fd_get_partials(ctypes.byref(shape), Workspace(ws_ptr, ws_bytes),
                                 *[ctypes.byref(o) for o in outs]))
     return tuple(o.value for o in outs)
-
-
-def fd_probe_stream_read(a, b, bytes_each, sink, stream=0):
-    _check(_lib.fd_probe_stream_read(a, b, bytes_each, sink, stream))
 
 
 def fd_logit_histogram(shape, q, k_cache, seq_lens, x_min, bin_width, n_bins, hist, min_max=None, stream=0):

@@ -36,11 +36,37 @@ def test_every_declared_symbol_is_exported(fdattn):
     assert sorted(fdattn.EXPORTS) == names, "binding and header disagree on the entry points"
 
 
+def test_the_read_probe_is_a_library_of_its_own(fdattn):
+    """The benchmark's streaming-read kernel is no entry point of the method: libfdattn does not export
+    it, libfdprobe.so does, as its own header declares."""
+    from paper_2311_01282_amd import fdprobe
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "fdprobe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(fd_[a-z_]+)\s*\(", text)))
+    assert names == ["fd_probe_stream_read"]
+    assert hasattr(ctypes.CDLL(fdprobe.LIB_PATH), "fd_probe_stream_read")
+    assert not hasattr(ctypes.CDLL(fdattn.LIB_PATH), "fd_probe_stream_read")
+    # host-side checks come before any launch
+    assert ctypes.CDLL(fdprobe.LIB_PATH).fd_probe_stream_read(None, None, 65536, None, None) == 1
+
+
+def test_workspace_layout_depends_on_the_slot_count_alone(fdattn):
+    """Shapes with the same number of (row, chunk) slots need the same bytes, and more slots never need fewer:
+    that is what lets one workspace, initialised once, serve every shape it can hold."""
+    a = fdattn.fd_workspace_bytes(fdattn.make_shape(4, 8, 8, 128, 1024, 256, 0.1))      # 32 rows x 4 chunks
+    b = fdattn.fd_workspace_bytes(fdattn.make_shape(1, 128, 128, 128, 256, 256, 0.1))   # 128 rows x 1 chunk
+    c = fdattn.fd_workspace_bytes(fdattn.make_shape(1, 1, 1, 128, 128 * 64, 64, 0.1))   # 1 row x 128 chunks
+    assert a == b == c
+    sizes = [fdattn.fd_workspace_bytes(fdattn.make_shape(1, 4, 4, 128, 256 * nc, 256, 0.1)) for nc in range(1, 40)]
+    assert sizes == sorted(sizes)
+
+
 def test_workspace_bytes(fdattn):
     sh = fdattn.make_shape(1, 32, 32, 128, 8192, 256, 0.0884)
     n = fdattn.fd_workspace_bytes(sh)
     rows, nc = 32, 32
-    need = rows * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4) + rows * (1 + 4) + 4
+    # per (row, chunk) slot: numerator, denominator, reference, chunk flag, slot record, arrival counter, and the
+    # per-row flag and list entry sized by slots too (so that the layout depends on the slot count alone)
+    need = rows * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4 + 1 + 4) + 4
     assert need <= n <= need + 16 * 256 and n % 256 == 0
     # unsupported or invalid shapes give 0
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0     # head_dim
@@ -49,7 +75,7 @@ def test_workspace_bytes(fdattn):
     for chunk in (64, 80, 1152, 3008, 4096):
         nc = -(-8192 // chunk)
         n = fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 8192, chunk, 0.1))
-        assert n >= 32 * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4)
+        assert n >= 32 * nc * (128 * 4 + 4 + 4 + 1 + 16 + 4 + 1 + 4)
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0     # heads
     assert fdattn.fd_workspace_bytes(fdattn.make_shape(1, 32, 32, 128, 0, 256, 0.1)) == 0       # max_seq
     # a ragged last chunk still gets a slot

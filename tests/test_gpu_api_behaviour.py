@@ -18,18 +18,19 @@ def H():
 
 
 def test_one_workspace_many_calls_and_shapes(oracle, H):
-    """One allocation serves different chunk sizes, entry points and problem shapes in
-    turn; it is re-initialised whenever the shape changes (the layout depends on it),
-    and repeated calls with one shape need no re-initialisation."""
+    """One allocation, initialised ONCE (with the smallest shape it will see), serves different
+    chunk sizes, entry points and problem shapes in turn, small after large and large after small:
+    the arrival counters sit at the end of the workspace whatever the shape, every call leaves them
+    zero, and no shape's data sections reach another shape's counters."""
     big = synth.make_case(B=2, Hq=4, Hkv=4, D=128, Smax=2048, seed=500, seq_lens=[2048, 900])
     small = synth.make_case(B=1, Hq=8, Hkv=2, D=128, Smax=640, seed=501, seq_lens=[600])
     synth.plant_keys(big, 2, 36.0, seed=502)
     dev = torch.device("cuda:0")
     nbytes = max(fdattn.fd_workspace_bytes(fdattn.make_shape(2, 4, 4, 128, 2048, 64, big["scale"])),
-                 fdattn.fd_workspace_bytes(fdattn.make_shape(1, 8, 2, 128, 640, 64, small["scale"])))
+                 fdattn.fd_workspace_bytes(fdattn.make_shape(1, 8, 2, 128, 640, 64, small["scale"]))) + 100   # (no multiple of 256)
     ws = torch.full((nbytes,), 0x5A, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
-    last_shape = None
+    fdattn.fd_workspace_init(fdattn.make_shape(1, 8, 2, 128, 640, 512, small["scale"]), ws.data_ptr(), nbytes, stream)
     want = {id(big): oracle.attn_exact(big["q"], big["k"], big["v"], big["seq_lens"], big["scale"]),
             id(small): oracle.attn_exact(small["q"], small["k"], small["v"], small["seq_lens"], small["scale"])}
     dev_t = {}
@@ -39,20 +40,55 @@ def test_one_workspace_many_calls_and_shapes(oracle, H):
     plan = [(big, "fd_decode_attn", 256), (small, "fd_decode_attn_gqa", 128), (big, "fd_decode_attn", 64),
             (small, "fd_decode_attn", 64), (big, "fd_decode_attn_multikernel", 512), (small, "fd_decode_attn_gqa", 64),
             (big, "fd_decode_attn", 1024), (big, "fd_decode_attn", 1024), (big, "fd_decode_attn_multikernel", 1024),
+            (big, "fd_decode_attn_sync", 128), (small, "fd_decode_attn_gqa", 320), (big, "fd_decode_attn", 64),
             (big, "fd_decode_attn", 1024)]
     for case, entry, chunk in plan:
         q, k, v, sl = dev_t[id(case)]
         shape = fdattn.make_shape(case["B"], case["Hq"], case["Hkv"], 128, case["Smax"], chunk, case["scale"])
         assert fdattn.fd_workspace_bytes(shape) <= nbytes
-        key = (case["B"], case["Hq"], case["Hkv"], case["Smax"], chunk)
-        if key != last_shape:
-            fdattn.fd_workspace_init(shape, ws.data_ptr(), nbytes, stream)
-            last_shape = key
         out = torch.full((case["B"], case["Hq"], 128), float("nan"), dtype=torch.float16, device=dev)
-        getattr(fdattn, entry)(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), synth.PHI,
-                               synth.BOUNDS, out.data_ptr(), ws.data_ptr(), nbytes, stream)
+        if entry == "fd_decode_attn_sync":
+            fdattn.fd_decode_attn_sync(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), out.data_ptr(),
+                                       ws.data_ptr(), nbytes, stream)
+        else:
+            getattr(fdattn, entry)(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), synth.PHI,
+                                   synth.BOUNDS, out.data_ptr(), ws.data_ptr(), nbytes, stream)
         torch.cuda.synchronize()
         H.assert_close(out.cpu().numpy().astype(np.float64), want[id(case)], "%s chunk %d" % (entry, chunk))
+
+
+def test_paged_caller_changes_max_seq_and_chunk_every_step(H):
+    """What the header tells a paged caller to do: pass the longest current length, rounded up to a page, as
+    max_seq and pick the chunk for it -- so the shape differs from step to step on one workspace that was
+    initialised once.  Sequences grow, one shrinks back (a finished request replaced by a new one)."""
+    from oracle import fd_paged_oracle as po
+    page, B, Hq = 64, 3, 4
+    cap = 4096
+    case = synth.make_case(B=B, Hq=Hq, Hkv=Hq, D=128, Smax=cap, seed=540, seq_lens=[cap, cap, cap])
+    k_pool, v_pool, table = synth.to_pages(case, page, seed=541)
+    dev = torch.device("cuda:0")
+    q, kp, vp = (torch.from_numpy(a).to(dev) for a in (case["q"], k_pool, v_pool))
+    nbytes = fdattn.fd_workspace_bytes(fdattn.make_shape(B, Hq, Hq, 128, cap, 64, case["scale"]))
+    ws = torch.full((nbytes,), 0xC3, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    fdattn.fd_workspace_init(fdattn.make_shape(B, Hq, Hq, 128, cap, 64, case["scale"]), ws.data_ptr(), nbytes, stream)
+    steps = [([100, 70, 10], None), ([1000, 700, 300], None), ([4096, 3000, 2000], None), ([130, 3001, 2001], None),
+             ([131, 64, 1], 64), ([2500, 65, 2], 1008), ([4096, 4096, 4096], None)]
+    for lens, forced_chunk in steps:
+        longest = -(-max(lens) // page) * page
+        chunk = forced_chunk or fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hq, 128, longest, 0, case["scale"]))
+        chunk = min(chunk, 64 * page)
+        shape = fdattn.make_shape(B, Hq, Hq, 128, longest, chunk, case["scale"])
+        assert fdattn.fd_workspace_bytes(shape) <= nbytes
+        tb = torch.from_numpy(np.ascontiguousarray(table[:, :longest // page])).to(dev)
+        sl_np = np.asarray(lens, dtype=np.int32)
+        sl = torch.from_numpy(sl_np).to(dev)
+        out = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device=dev)
+        fdattn.fd_decode_attn_paged(shape, q.data_ptr(), kp.data_ptr(), vp.data_ptr(), tb.data_ptr(), page, k_pool.shape[0],
+                                    sl.data_ptr(), synth.PHI, synth.BOUNDS, out.data_ptr(), ws.data_ptr(), nbytes, stream)
+        torch.cuda.synchronize()
+        want = po.attn_exact(case["q"], k_pool, v_pool, table, page, sl_np, case["scale"], nthreads=8)
+        H.assert_close(out.cpu().numpy().astype(np.float64), want, "lengths %s, max_seq %d, chunk %d" % (lens, longest, chunk))
 
 
 def test_side_stream_and_back_to_back_calls(oracle, H):
@@ -86,10 +122,11 @@ def test_flag_list_call_and_read_probe(oracle, H):
     # the probe only reads; it must accept the K and V buffers and reject odd sizes
     sink = torch.zeros(1, dtype=torch.int32, device=dc.dev)
     nbytes = dc.k.numel() * 2
-    fdattn.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes, sink.data_ptr(), 0)
+    from paper_2311_01282_amd import fdprobe
+    fdprobe.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes, sink.data_ptr(), 0)
     torch.cuda.synchronize()
-    with pytest.raises(fdattn.FdError):
-        fdattn.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes - 2, sink.data_ptr(), 0)
+    with pytest.raises(RuntimeError):
+        fdprobe.fd_probe_stream_read(dc.k.data_ptr(), dc.v.data_ptr(), nbytes - 2, sink.data_ptr(), 0)
 
 
 @pytest.mark.parametrize("Smax,lens,chunk", [(100, [100], 256), (64, [1], 64), (300, [299], 1024), (4097, [4097], 512)])

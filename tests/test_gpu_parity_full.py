@@ -37,6 +37,14 @@ def check(oracle, H, name, entry, chunks, poison=False):
         cf, rf, n, rows = dc.flags()
         assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
         assert n == int(orf.sum()) and rows.tolist() == np.flatnonzero(orf.reshape(-1)).tolist()
+        # the literal chain (partial / flag reduction / atomic-free combine / whole-row recomputation of flagged
+        # rows / synchronized merge): outputs, chunk and row flags, the ascending list and its count
+        got_chain = dc.run("fd_decode_attn_multikernel")
+        H.assert_close(got_chain, want, "%s chain chunk %d" % (name, chunk))
+        ccf, crf, cn, crows = dc.flags()
+        assert np.array_equal(ccf, ocf) and np.array_equal(crf, orf)
+        assert cn == int(orf.sum()) and crows.tolist() == np.flatnonzero(orf.reshape(-1)).tolist()
+        assert np.abs(got - got_chain)[orf == 0].max() <= 1e-3
         # the synchronized scheme on every row must agree with the unified path (unflagged rows)
         got_sync = dc.run("fd_decode_attn_sync")
         H.assert_close(got_sync, want, "%s sync chunk %d" % (name, chunk))

@@ -11,38 +11,51 @@ in the 256 MB last-level cache: what a multi-layer model does for every generate
 token.  All inputs are resident in HBM before the clock starts.  Prints ONE JSON
 line.
 
+Timing protocol (every figure of the line): HIP events on the launch stream around
+``max(K, 200)`` back-to-back calls after ``max(W, 20)`` warm-up calls, repeated
+``--repeats`` (5) times; the figure reported is the MEDIAN repeat, its fastest repeat
+is given next to it.  A short ``--steps`` therefore never shortens the timed loop
+below 200 calls (one synchronisation is 2-4 % of a 20-call loop of this size).  The
+wall clock around the same loops is reported too (``wall_us_per_layer_step``).
+
 ``value`` is the effective KV-read rate of the whole call: valid K+V bytes of one
-layer divided by the mean time per step (``us_per_layer_step``).  ``roofline``
-times the dominant kernel (the chunk kernel) alone with HIP events on the launch
-stream and sets it against the HBM peak and against a plain streaming read of the
-same buffers.  ``cpu_baseline`` times the fp64 oracle on the host cores.
-Secondary measurements (``chunk_sweep``, ``sync_baseline``, ``overflow``) use
-shorter loops of their own after the timed region.
+layer divided by the median time per step.  ``roofline`` is the dominant kernel (the
+chunk kernel) against the HBM peak -- the very same measurement when the call is a
+single launch -- and against a plain streaming read of the same buffers.
+``cpu_baseline`` times the fp64 oracle on the host cores.  ``workloads`` holds the
+other four workloads of the benchmark set, each with its parity against the oracle,
+the overflow overhead of the 32K workload (fused call and literal chain, 2 / 1 / 0
+flagged rows) and the prefill figure at 8K tokens.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E, published peak
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix-core peak
+DTYPE = "f32"               # the arithmetic type: fp16 q/K/V/out in memory, every sum and exponential in fp32
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=5, help="repeats of the timed loop; median and min are reported")
     ap.add_argument("--workload", default="c1_b1_h32_s8192")
     ap.add_argument("--chunk", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV caches to cycle through (0 = auto)")
     ap.add_argument("--entry", default="auto", choices=["auto", "fd_decode_attn", "fd_decode_attn_gqa",
                                                         "fd_decode_attn_multikernel", "fd_decode_attn_sync"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline and overflow A/B")
+    ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline, paged / append variants")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the block with the other workloads, overflow and prefill")
     ap.add_argument("--prefill", type=int, default=0, metavar="S",
                     help="time the prompt phase instead (fd_prefill_attn): batch 1, 32 heads, prompt of S tokens")
     ap.add_argument("--prefill-heads", type=int, nargs=2, default=[32, 32], metavar=("HQ", "HKV"),
@@ -53,18 +66,176 @@ def parse():
     return ap.parse_args()
 
 
-MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix-core peak
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def prefill(args):
+class Timer:
+    """HIP events on torch's current stream (the stream every call below is enqueued on)."""
+
+    def __init__(self, torch, steps, warmup, repeats):
+        self.torch = torch
+        self.calls = max(int(steps), 200)
+        self.warmup = max(int(warmup), 20)
+        self.repeats = max(int(repeats), 1)
+
+    def __call__(self, fn, calls=None, warmup=None, repeats=None):
+        """fn(i) enqueues call i.  Returns seconds per call: dict(median, min, wall_median, all)."""
+        torch = self.torch
+        calls = calls or self.calls
+        warmup = self.warmup if warmup is None else warmup
+        repeats = repeats or self.repeats
+        for i in range(warmup):
+            fn(i)
+        ev, wall = [], []
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record()
+            for i in range(calls):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            wall.append((time.perf_counter() - t0) / calls)
+            ev.append(e0.elapsed_time(e1) * 1e-3 / calls)
+        return {"median": statistics.median(ev), "min": min(ev), "wall_median": statistics.median(wall), "all": ev,
+                "calls": calls, "warmup": warmup, "repeats": repeats}
+
+
+def us(x, nd=2):
+    return round(x * 1e6, nd)
+
+
+class Workload:
+    """One of synth.CONFIGS on the device: layer 0 from the seeded host generator (the oracle sees the
+    same bits), the other layers of the cold-cache rotation drawn on the device (same distribution)."""
+
+    def __init__(self, torch, np, fdattn, synth, name, layers=0, dev=None):
+        self.torch, self.np, self.fdattn, self.synth, self.name = torch, np, fdattn, synth, name
+        self.dev = dev
+        cfg = self.cfg = dict(synth.CONFIGS[name])
+        B, Hq, Hkv, D, Smax = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"]
+        self.B, self.Hq, self.Hkv, self.D, self.Smax = B, Hq, Hkv, D, Smax
+        self.grouped = 2 <= Hq // Hkv <= 16
+        self.case0 = case0 = synth.make_config(name, layer=0)
+        self.seq_lens_np = case0["seq_lens"]
+        self.valid_keys = int(np.clip(self.seq_lens_np, 0, Smax).sum())
+        self.kv_bytes = self.valid_keys * Hkv * D * 2 * 2           # K and V, fp16
+        padded_bytes = B * Hkv * Smax * D * 2 * 2
+        self.layers = layers or max(2, min(64, -(-(1 << 30) // padded_bytes)))
+        if name.startswith("c1") and not layers:
+            self.layers = 32                                         # 4 GiB: what a 32-layer model holds
+        gen = self.gen = torch.Generator(device=dev)
+        gen.manual_seed(cfg["seed"])
+        self.qs, self.ks, self.vs = [], [], []
+        for layer in range(self.layers):
+            if layer == 0:
+                self.qs.append(torch.from_numpy(case0["q"]).to(dev))
+                self.ks.append(torch.from_numpy(case0["k"]).to(dev))
+                self.vs.append(torch.from_numpy(case0["v"]).to(dev))
+            else:
+                self.qs.append(torch.randn((B, Hq, D), generator=gen, device=dev, dtype=torch.float32).half())
+                self.ks.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
+                self.vs.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
+        # planted overflow keys (layer 0 has them from the host generator): same rows and positions in
+        # every other layer, gamma * q / |q| computed from that layer's q
+        self.planted = case0["planted"]
+        self.saved_keys = []
+        for layer in range(1, self.layers):
+            for (b, h, pos) in self.planted:
+                qv = self.qs[layer][b, h].float()
+                self.saved_keys.append((layer, b, h, pos, self.ks[layer][b, h, pos].clone()))
+                self.ks[layer][b, h, pos] = (cfg["plant_gamma"] * qv / qv.norm()).half()
+        self.seq_lens = torch.from_numpy(self.seq_lens_np).to(dev)
+        self.out = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
+        self.stream = torch.cuda.current_stream(dev).cuda_stream
+        self.picked = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, D, Smax, 0, 1.0))
+        # the 1K workload's chunk is fixed at 256 by its definition; elsewhere the split is the library's choice
+        self.default_chunk = cfg["chunk"] if name.startswith("c0") else self.picked
+        self.default_entry = "fd_decode_attn_gqa" if self.grouped else "fd_decode_attn"
+
+    def unplant(self, keep):
+        """Put the original keys back for all planted rows but the first `keep`."""
+        torch = self.torch
+        for (b, h, pos), orig in list(zip(self.planted, self.case0["planted_original_keys"]))[keep:]:
+            self.ks[0][b, h, pos] = torch.from_numpy(orig).to(self.dev)
+        for (layer, b, h, pos, orig) in self.saved_keys:
+            if (b, h, pos) in self.planted[keep:]:
+                self.ks[layer][b, h, pos] = orig
+
+    def runner(self, chunk=None, entry=None):
+        return Runner(self, chunk or self.default_chunk, entry or self.default_entry)
+
+    def parity(self, run, ncpu):
+        """Layer 0 of what is being timed against the oracle: (max-abs, elements beyond 1 fp16 ulp, elements,
+        oracle seconds)."""
+        from oracle import fd_oracle
+        np, c = self.np, self.case0
+        run.step(0)
+        self.torch.cuda.synchronize()
+        got = self.out.cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        want = fd_oracle.attn_exact(c["q"], c["k"], c["v"], self.seq_lens_np, c["scale"], nthreads=ncpu)
+        t_cpu = time.perf_counter() - t0
+        max_abs = float(np.abs(got - want).max())
+        want16 = want.astype(np.float16).astype(np.float64)
+        ulp = np.maximum(np.spacing(np.abs(want).astype(np.float16)).astype(np.float64), 2.0 ** -24)
+        return max_abs, int((np.abs(got - want16) > ulp).sum()), int(got.size), t_cpu
+
+
+class Runner:
+    def __init__(self, wl, chunk, entry):
+        fdattn = wl.fdattn
+        self.wl, self.entry, self.chunk = wl, entry, chunk
+        self.shape = fdattn.make_shape(wl.B, wl.Hq, wl.Hkv, wl.D, wl.Smax, chunk, wl.case0["scale"])
+        self.ws_bytes = fdattn.fd_workspace_bytes(self.shape)
+        self.ws = wl.torch.empty(self.ws_bytes, dtype=wl.torch.uint8, device=wl.dev)
+        fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, wl.stream)
+        gqa = entry == "fd_decode_attn_gqa"
+        self.gqa = gqa
+        nc = -(-wl.Smax // chunk)
+        wgs = wl.B * (wl.Hkv if gqa else wl.Hq) * nc
+        # the library's own rule: the grouped kernel finishes its rows itself up to 256 workgroups and 8 chunks
+        # per row, the per-row kernel up to 1024 workgroups; beyond, the row epilogue is a launch of its own
+        fused = entry in ("fd_decode_attn", "fd_decode_attn_gqa")
+        self.single_launch = fused and ((wgs <= 256 and nc <= 8) if gqa else wgs <= 1024)
+        self.launches = 1 if self.single_launch else (3 if entry == "fd_decode_attn_multikernel" else 2)
+        self.grid = (wl.B * wl.Hkv * nc) if gqa else 8 * ((wl.B * wl.Hq + 7) // 8) * nc
+
+    def kernel_name(self):
+        """Template arguments as the profiler prints them: <chunk capacity, paged, wavefronts> for the grouped
+        kernel, <chunk capacity, in-kernel hand-over, paged, early loads> for the per-row one."""
+        cap = 64
+        while cap < self.chunk:
+            cap *= 2
+        if self.gqa:
+            return "decode_fused_gqa_kernel<%d, false, 4>" % cap
+        early = self.single_launch and self.grid <= 256
+        return "decode_fused_kernel<%d, %s, false, %s>" % (cap, "true" if self.single_launch else "false",
+                                                           "true" if early else "false")
+
+    def step(self, i):
+        wl, fdattn = self.wl, self.wl.fdattn
+        l = i % wl.layers
+        a = (self.shape, wl.qs[l].data_ptr(), wl.ks[l].data_ptr(), wl.vs[l].data_ptr(), wl.seq_lens.data_ptr())
+        if self.entry == "fd_decode_attn_sync":
+            fdattn.fd_decode_attn_sync(*a, wl.out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, wl.stream)
+        else:
+            getattr(fdattn, self.entry)(*a, wl.synth.PHI, wl.synth.BOUNDS, wl.out.data_ptr(), self.ws.data_ptr(),
+                                        self.ws_bytes, wl.stream)
+
+    def chunk_kernel(self, i):
+        wl, fdattn = self.wl, self.wl.fdattn
+        l = i % wl.layers
+        f = fdattn.fd_decode_attn_gqa_partial if self.gqa else fdattn.fd_decode_attn_partial
+        f(self.shape, wl.qs[l].data_ptr(), wl.ks[l].data_ptr(), wl.vs[l].data_ptr(), wl.seq_lens.data_ptr(), wl.synth.PHI,
+          wl.synth.BOUNDS, self.ws.data_ptr(), self.ws_bytes, wl.stream)
+
+
+def prefill_measure(torch, np, fdattn, synth, dev, S, H, Hkv, timer):
     """Prompt phase: one fd_prefill_attn call per step on a seeded synthetic prompt."""
-    import numpy as np
-    import torch
-    from paper_2311_01282_amd import fdattn, synth
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    B, D, S = 1, 128, args.prefill
-    H, Hkv = args.prefill_heads
+    B, D = 1, 128
     scale = float(np.float32(1.0 / np.sqrt(D)))
     gen = torch.Generator(device=dev)
     gen.manual_seed(6000 + S)
@@ -77,7 +248,7 @@ def prefill(args):
     ws = torch.empty(nws, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
 
-    def step():
+    def step(i=0):
         fdattn.fd_prefill_attn(shape, q.data_ptr(), k.data_ptr(), v.data_ptr(), sl.data_ptr(), synth.PHI, synth.BOUNDS,
                                out.data_ptr(), ws.data_ptr(), nws, stream)
     # correctness of what is timed: a seeded sample of rows against the oracle
@@ -95,39 +266,92 @@ def prefill(args):
     got = out.cpu().numpy().astype(np.float64)[rows[:, 0], rows[:, 1], rows[:, 2]]
     max_abs = float(np.abs(got - want).max())
     if not (max_abs <= 2e-3):
-        print("bench.py: GPU prefill result differs from the oracle (max-abs %.3e)" % max_abs, file=sys.stderr)
-        return 1
-    steps, warmup = max(5, args.steps // 32), max(2, args.warmup // 16)
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    sec = (time.perf_counter() - t0) / steps
+        raise RuntimeError("GPU prefill result differs from the oracle (max-abs %.3e)" % max_abs)
+    # a call is about 1 ms at 8K tokens: about 50 ms of calls per repeat, 20 to 200 calls
+    calls = max(20, min(200, int(0.05 / (1e-3 * max(S / 8192.0, 1e-2) ** 2))))
+    t = timer(step, calls=calls, warmup=5)
     pairs = B * H * S * (S + 1) // 2                      # (query, key) pairs under the causal mask
     flops = 4.0 * D * pairs                               # q.k and p.v, multiply + add
     cpu_pairs = int((rows[:, 2] + 1).sum())
+    return {"S": S, "H": H, "Hkv": Hkv, "t": t, "flops": flops, "max_abs": max_abs, "t_cpu": t_cpu, "cpu_pairs": cpu_pairs,
+            "rows": len(rows), "ncpu": ncpu}
+
+
+def prefill(args):
+    import numpy as np
+    import torch
+    from paper_2311_01282_amd import fdattn, synth
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    H, Hkv = args.prefill_heads
+    timer = Timer(torch, args.steps, args.warmup, args.repeats)
+    try:
+        m = prefill_measure(torch, np, fdattn, synth, dev, args.prefill, H, Hkv, timer)
+    except RuntimeError as e:
+        print("bench.py: %s" % e, file=sys.stderr)
+        return 1
+    S, t, flops, D = m["S"], m["t"], m["flops"], 128
+    sec = t["median"]
     line = {
         "metric": "prefill_attention_throughput", "value": round(flops / sec / 1e12, 1), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(sec * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "n_gpus": 1, "steps": t["calls"], "warmup": t["warmup"], "repeats": t["repeats"], "ms_per_step": round(sec * 1e3, 4),
+        "ms_per_step_min": round(t["min"] * 1e3, 4), "timing": "HIP events, median of repeats",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": "prefill_b1_h%d%s_s%d" % (H, "" if H == Hkv else "x%d" % Hkv, S), "entry": "fd_prefill_attn",
-                   "batch": B, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": D, "prompt": S, "causal": True, "phi": synth.PHI,
+                   "batch": 1, "n_q_heads": H, "n_kv_heads": Hkv, "head_dim": D, "prompt": S, "causal": True, "phi": synth.PHI,
                    "bounds": list(synth.BOUNDS), "kv_dtype": "f16", "launches_per_step": 2},
-        "parity_max_abs_vs_oracle": max_abs,
+        "parity_max_abs_vs_oracle": m["max_abs"],
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / sec / 1e12, 1),
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(flops / sec / 1e12 / MFMA_PEAK_TFLOPS, 4),
                      "algorithmic_flops_per_launch": flops,
-                     "note": "whole call (transpose pass + attention); useful flops 4*D per causal (query, key) pair; "
-                             "the kernel issues 2x that on the matrix cores (bf16 hi+lo operands)", "traffic": None},
-        "cpu_baseline": {"value": round(4.0 * D * cpu_pairs / t_cpu / 1e12, 6), "unit": "TFLOP/s", "cores": ncpu,
+                     "note": "whole call (transpose pass + attention); useful flops 4*D per causal (query, key) pair",
+                     "traffic": None},
+        "cpu_baseline": {"value": round(4.0 * D * m["cpu_pairs"] / m["t_cpu"] / 1e12, 6), "unit": "TFLOP/s", "cores": m["ncpu"],
                          "kind": "oracle", "sample": "%d sampled query rows of the same prompt (%d query-key pairs), fp64"
-                                                      % (len(rows), cpu_pairs)},
+                                                      % (m["rows"], m["cpu_pairs"])},
     }
     print(json.dumps(line))
     return 0
+
+
+def workload_summary(wl, run, timer, ncpu):
+    """Compact record of one workload: the whole call, event-timed, and its parity against the oracle."""
+    max_abs, beyond, n_el, _ = wl.parity(run, ncpu)
+    t = timer(run.step, repeats=3)
+    gbs = wl.kv_bytes / t["median"] / 1e9
+    rec = {"entry": run.entry, "chunk": run.chunk, "launches_per_step": run.launches, "layers_cycled": wl.layers,
+           "kv_bytes_per_step": wl.kv_bytes,
+           "us_per_layer_step": us(t["median"]), "us_min": us(t["min"]), "wall_us": us(t["wall_median"]),
+           "kv_gbs": round(gbs, 1), "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+           "frac": round(gbs / HBM_PEAK_GBS, 4),
+           "parity_max_abs_vs_oracle": max_abs, "parity_elements_beyond_1_fp16_ulp": beyond, "parity_elements": n_el}
+    if not run.single_launch and run.entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
+        tk = timer(run.chunk_kernel, repeats=3)
+        rec["chunk_kernel_us"] = us(tk["median"])
+        rec["chunk_kernel_frac"] = round(wl.kv_bytes / tk["median"] / 1e9 / HBM_PEAK_GBS, 4)
+    return rec
+
+
+def overflow_ab(wl, timer, chunk):
+    """Overflow stress: the same tensors with all planted keys in, all but the first row's taken out, none left;
+    the fused call and the literal chain.  Leaves the workload without planted keys."""
+    fused = wl.runner(chunk, "fd_decode_attn")
+    chain = wl.runner(chunk, "fd_decode_attn_multikernel")
+    res = {"rows": wl.B * wl.Hq, "rows_flagged": len(wl.planted), "chunk": chunk}
+    t = {}
+    for keep, tag in ((len(wl.planted), "with"), (1, "one_row"), (0, "without")):
+        if keep < len(wl.planted):
+            wl.unplant(keep)
+        t["fused_" + tag] = timer(fused.step, repeats=3)["median"]
+        t["chain_" + tag] = timer(chain.step, repeats=3)["median"]
+    for k, v in t.items():
+        res["us_" + k] = us(v)
+    res["overhead_pct"] = round(100.0 * (t["fused_with"] / t["fused_without"] - 1.0), 2)
+    res["overhead_one_row_pct"] = round(100.0 * (t["fused_one_row"] / t["fused_without"] - 1.0), 2)
+    res["chain_overhead_pct"] = round(100.0 * (t["chain_with"] / t["chain_without"] - 1.0), 2)
+    res["chain_overhead_one_row_pct"] = round(100.0 * (t["chain_one_row"] / t["chain_without"] - 1.0), 2)
+    res["target_pct"] = 5.0
+    return res
 
 
 def main():
@@ -148,107 +372,19 @@ def main():
         return prefill(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    timer = Timer(torch, args.steps, args.warmup, args.repeats)
+    ncpu = min(os.cpu_count() or 1, 16)
 
-    cfg = dict(synth.CONFIGS[args.workload])
-    B, Hq, Hkv, D, Smax = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"]
-    grouped = Hq != Hkv
-    entry = args.entry
-    if entry == "auto":
-        entry = "fd_decode_attn_gqa" if grouped else "fd_decode_attn"
-    # the 1K workload's chunk is fixed at 256; elsewhere the split is the library's to choose
-    # (for the 8K workload, swept over {256, 512, 1024}, that is the best of the three)
-    picked = fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, D, Smax, 0, 1.0))
-    default_chunk = cfg["chunk"] if args.workload.startswith("c0") else picked
-    chunk = args.chunk or default_chunk
-
-    # ---- layer 0 from the seeded host generator (the oracle sees the same bits) ----
-    case0 = synth.make_config(args.workload, layer=0)
-    seq_lens_np = case0["seq_lens"]
-    valid_keys = int(np.clip(seq_lens_np, 0, Smax).sum())
-    kv_bytes = valid_keys * Hkv * D * 2 * 2           # K and V, fp16
-    padded_bytes = B * Hkv * Smax * D * 2 * 2
-    layers = args.layers or max(2, min(64, -(-(1 << 30) // padded_bytes)))
-    if args.workload.startswith("c1") and not args.layers:
-        layers = 32
-
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(cfg["seed"])
-    qs, ks, vs = [], [], []
-    for layer in range(layers):
-        if layer == 0:
-            qs.append(torch.from_numpy(case0["q"]).to(dev))
-            ks.append(torch.from_numpy(case0["k"]).to(dev))
-            vs.append(torch.from_numpy(case0["v"]).to(dev))
-        else:   # same distribution, drawn on the device to keep set-up short
-            qs.append(torch.randn((B, Hq, D), generator=gen, device=dev, dtype=torch.float32).half())
-            ks.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
-            vs.append(torch.randn((B, Hkv, Smax, D), generator=gen, device=dev, dtype=torch.float32).half())
-    # planted overflow keys (layer 0 has them from the host generator): same rows and
-    # positions in every other layer, gamma * q / |q| computed from that layer's q
-    planted = case0["planted"]
-    saved_keys = []
-    for layer in range(layers):
-        for (b, h, pos) in planted:
-            if layer > 0:
-                qv = qs[layer][b, h].float()
-                saved_keys.append((layer, b, h, pos, ks[layer][b, h, pos].clone()))
-                ks[layer][b, h, pos] = (cfg["plant_gamma"] * qv / qv.norm()).half()
-    seq_lens = torch.from_numpy(seq_lens_np).to(dev)
-    stream = torch.cuda.current_stream(dev).cuda_stream
+    log("building %s" % args.workload)
+    wl = Workload(torch, np, fdattn, synth, args.workload, args.layers, dev)
+    B, Hq, Hkv, D, Smax = wl.B, wl.Hq, wl.Hkv, wl.D, wl.Smax
+    entry = wl.default_entry if args.entry == "auto" else args.entry
+    chunk = args.chunk or wl.default_chunk
+    run = wl.runner(chunk, entry)
+    layers, kv_bytes, stream = wl.layers, wl.kv_bytes, wl.stream
+    qs, ks, vs, seq_lens, out = wl.qs, wl.ks, wl.vs, wl.seq_lens, wl.out
     phi, bounds = synth.PHI, synth.BOUNDS
-    out = torch.empty((B, Hq, D), dtype=torch.float16, device=dev)
 
-    class Runner:
-        def __init__(self, chunk, entry):
-            self.entry = entry
-            self.shape = fdattn.make_shape(B, Hq, Hkv, D, Smax, chunk, case0["scale"])
-            self.ws_bytes = fdattn.fd_workspace_bytes(self.shape)
-            self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
-            fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, stream)
-            gqa = entry == "fd_decode_attn_gqa"
-            nc = -(-Smax // chunk)
-            wgs = B * (Hkv if gqa else Hq) * nc
-            # the library's own rule: the grouped kernel finishes its rows itself up to 256 workgroups and 8 chunks
-            # per row, the per-row kernel up to 1024 workgroups; beyond, the row epilogue is a launch of its own
-            self.single_launch = ((wgs <= 256 and nc <= 8) if gqa else wgs <= 1024) and entry in ("fd_decode_attn", "fd_decode_attn_gqa")
-
-        def step(self, i):
-            l = i % layers
-            a = (self.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr())
-            if self.entry == "fd_decode_attn_sync":
-                fdattn.fd_decode_attn_sync(*a, out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, stream)
-            else:
-                getattr(fdattn, self.entry)(*a, phi, bounds, out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, stream)
-
-        def chunk_kernel(self, i):
-            l = i % layers
-            f = fdattn.fd_decode_attn_gqa_partial if self.entry == "fd_decode_attn_gqa" else fdattn.fd_decode_attn_partial
-            f(self.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr(), phi, bounds,
-              self.ws.data_ptr(), self.ws_bytes, stream)
-
-    def wall(fn, steps, warmup):
-        for i in range(warmup):
-            fn(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            fn(i)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
-
-    def events(fn, steps, warmup):
-        for i in range(warmup):
-            fn(i)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(steps):
-            fn(i)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e-3 / steps
-
-    run = Runner(chunk, entry)
     if args.calibrate_copy:
         src = torch.ones(128 << 20, dtype=torch.float16, device=dev)
         dst = torch.empty_like(src)
@@ -258,45 +394,30 @@ def main():
         del src, dst
 
     # ---- correctness of what is being timed: layer 0 against the oracle ----
-    from oracle import fd_oracle
-    ncpu = min(os.cpu_count() or 1, 16)
-    run.step(0)
-    torch.cuda.synchronize()
-    got = out.cpu().numpy().astype(np.float64)
-    t0 = time.perf_counter()
-    want = fd_oracle.attn_exact(case0["q"], case0["k"], case0["v"], seq_lens_np, case0["scale"], nthreads=ncpu)
-    t_cpu = time.perf_counter() - t0
-    max_abs = float(np.abs(got - want).max())
+    max_abs, beyond_1ulp, n_elements, t_cpu = wl.parity(run, ncpu)
     if not (max_abs <= 2e-3):
         print("bench.py: GPU result differs from the oracle (max-abs %.3e)" % max_abs, file=sys.stderr)
         return 1
-    # diagnostic: output elements more than one fp16 unit in the last place away from the rounded oracle value
-    want16 = want.astype(np.float16).astype(np.float64)
-    ulp = np.maximum(np.spacing(np.abs(want).astype(np.float16)).astype(np.float64), 2.0 ** -24)
-    beyond_1ulp = int((np.abs(got - want16) > ulp).sum())
 
     # ---- timed region: the whole call ----
-    sec_per_step = wall(run.step, args.steps, args.warmup)
+    log("timing %s / %s, chunk %d: %d repeats of %d calls" % (args.workload, entry, chunk, timer.repeats, timer.calls))
+    t_call = timer(run.step)
+    sec_per_step = t_call["median"]
     value = kv_bytes / sec_per_step / 1e9
 
-    short = max(50, args.steps // 4)
-    # ---- dominant kernel alone, HIP events on the launch stream ----
+    # ---- dominant kernel: the chunk kernel (the whole call when it is a single launch) ----
     roofline = None
-    if entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
-        # template arguments as the profiler prints them: <chunk, paged, wavefronts> for the grouped kernel,
-        # <chunk, in-kernel hand-over, paged, early loads (launches of at most 256 workgroups)> for the per-row one
-        grid = 8 * ((B * Hq + 7) // 8) * ((Smax + chunk - 1) // chunk)
-        early = run.single_launch and grid <= 256
-        kname = ("decode_fused_gqa_kernel<%d, false, 4>" % chunk if entry == "fd_decode_attn_gqa" else
-                 "decode_fused_kernel<%d, %s, false, %s>" % (chunk, "true" if run.single_launch else "false",
-                                                             "true" if early else "false"))
-        k_sec = events(run.step if run.single_launch else run.chunk_kernel, args.steps, args.warmup)
+    fused_entries = ("fd_decode_attn", "fd_decode_attn_gqa")
+    if entry in fused_entries:
+        t_k = t_call if run.single_launch else timer(run.chunk_kernel)
+        k_sec = t_k["median"]
         achieved = kv_bytes / k_sec / 1e9
+        kname = run.kernel_name()
         roofline = {"bound": "hbm", "kernel": kname,
-                    "launch": "the whole call (single launch)" if run.single_launch else
-                              "chunk kernel alone; the call adds one row-epilogue launch",
+                    "launch": "the whole call (single launch): the same measurement as `value`" if run.single_launch else
+                              "chunk kernel alone (timed through the *_partial entry point); the call adds one row-epilogue launch",
                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(achieved / HBM_PEAK_GBS, 4), "us_per_launch": round(k_sec * 1e6, 2),
+                    "frac": round(achieved / HBM_PEAK_GBS, 4), "us_per_launch": us(k_sec), "us_per_launch_min": us(t_k["min"]),
                     "algorithmic_bytes_per_launch": kv_bytes, "traffic": None}
         # HBM bytes per launch from the committed rocprofv3 counter runs (same kernel and workload)
         try:
@@ -308,39 +429,39 @@ def main():
         except (OSError, ValueError, KeyError):
             pass
         nbytes_each = B * Hkv * Smax * D * 2
-        if nbytes_each % 65536 == 0 and valid_keys == B * Smax:
-            # plain streaming read of the same K and V buffers: the measured ceiling
-            sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        if nbytes_each % 65536 == 0 and wl.valid_keys == B * Smax:
+            # plain streaming read of the same K and V buffers (libfdprobe, not part of libfdattn): the measured ceiling
             from paper_2311_01282_amd import fdprobe
-            p_sec = events(lambda i: fdprobe.fd_probe_stream_read(ks[i % layers].data_ptr(), vs[i % layers].data_ptr(),
-                                                                  nbytes_each, sink.data_ptr(), stream),
-                           short, 10)
+            sink = torch.zeros(1, dtype=torch.int32, device=dev)
+            t_p = timer(lambda i: fdprobe.fd_probe_stream_read(ks[i % layers].data_ptr(), vs[i % layers].data_ptr(),
+                                                                nbytes_each, sink.data_ptr(), stream), repeats=3)
+            p_sec = t_p["median"]
+            roofline["stream_read_us"] = us(p_sec)
             roofline["stream_read_ceiling_gbs"] = round(2 * nbytes_each / p_sec / 1e9, 1)
             roofline["frac_of_stream_read_ceiling"] = round((kv_bytes / k_sec) / (2 * nbytes_each / p_sec), 4)
 
     extras = {}
     if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
-        # chunk sweep (us per layer-step of the whole call)
+        log("extras: chunk sweep, baselines, graph replay")
+        # chunk sweep (us per layer-step of the whole call; event-timed like the headline, 3 repeats)
         sweep = {}
         for c in sorted({256, 512, 1024, chunk}):
-            r = run if c == chunk else Runner(c, entry)
-            sweep[str(c)] = round(wall(r.step, short, 10) * 1e6, 2)
+            sweep[str(c)] = us(t_call["median"] if c == chunk else timer(wl.runner(c, entry).step, repeats=3)["median"])
         extras["chunk_sweep_us"] = sweep
         # the synchronized scheme on every row (Eq. 2): what the method replaces
-        rs = Runner(chunk, "fd_decode_attn_sync")
-        extras["sync_baseline_us"] = round(wall(rs.step, short, 10) * 1e6, 2)
-        if not grouped:
-            rm = Runner(chunk, "fd_decode_attn_multikernel")
-            extras["multikernel_chain_us"] = round(wall(rm.step, short, 10) * 1e6, 2)
+        extras["sync_baseline_us"] = us(timer(wl.runner(chunk, "fd_decode_attn_sync").step, repeats=3)["median"])
+        if not wl.grouped:
+            extras["multikernel_chain_us"] = us(timer(wl.runner(chunk, "fd_decode_attn_multikernel").step, repeats=3)["median"])
         # statistics pass of the calibration (reads K only): histogram of the scaled logits
         n_bins = 256
         hist = torch.zeros(n_bins + 2, dtype=torch.int64, device=dev)
+
         def stats(i):
             l = i % layers
             fdattn.fd_logit_histogram(run.shape, qs[l].data_ptr(), ks[l].data_ptr(), seq_lens.data_ptr(), -16.0, 0.125,
                                       n_bins, hist.data_ptr(), None, stream)
-        t_stats = wall(stats, short, 10)
-        extras["logit_histogram"] = {"us": round(t_stats * 1e6, 2), "k_bytes": kv_bytes // 2,
+        t_stats = timer(stats, repeats=3)["median"]
+        extras["logit_histogram"] = {"us": us(t_stats), "k_bytes": kv_bytes // 2,
                                      "k_gbs": round(kv_bytes / 2 / t_stats / 1e9, 1),
                                      "note": "K read once per query head; with grouped heads the repeats hit in L2"}
         # the same rotation of calls recorded once by a stream capture and replayed as a graph
@@ -355,50 +476,20 @@ def main():
                         a = (run.shape, qs[l].data_ptr(), ks[l].data_ptr(), vs[l].data_ptr(), seq_lens.data_ptr())
                         getattr(fdattn, entry)(*a, phi, bounds, out.data_ptr(), run.ws.data_ptr(), run.ws_bytes, side.cuda_stream)
             torch.cuda.synchronize()
-            reps = max(2, short // layers)
-            for _ in range(2):
-                graph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(reps):
-                graph.replay()
-            torch.cuda.synchronize()
-            extras["graph_replay_us"] = round((time.perf_counter() - t0) / (reps * layers) * 1e6, 2)
+            reps = max(2, timer.calls // layers)
+            t_g = timer(lambda i: graph.replay(), calls=reps, warmup=2, repeats=3)
+            extras["graph_replay_us"] = us(t_g["median"] / layers)
             del graph
         except RuntimeError as e:                       # capture not available: report, do not fail the run
             extras["graph_replay_us"] = None
             extras["graph_replay_error"] = str(e)[:200]
         # cache-resident figure: the same KV set every call (fits the last-level cache at c0 and c1)
-        extras["hot_cache_us"] = round(wall(lambda i: run.step(0), short, 10) * 1e6, 2)
-        if planted:
-            # overflow A/B on the same tensors: all planted keys in, then all but the first
-            # row's taken out, then none left
-            def unplant(keep):
-                for (b, h, pos), orig in list(zip(planted, case0["planted_original_keys"]))[keep:]:
-                    ks[0][b, h, pos] = torch.from_numpy(orig).to(dev)
-                for (layer, b, h, pos, orig) in saved_keys:
-                    if (b, h, pos) in planted[keep:]:
-                        ks[layer][b, h, pos] = orig
-            t_with = wall(run.step, short, 10)
-            unplant(1)
-            t_one = wall(run.step, short, 10)
-            unplant(0)
-            t_without = wall(run.step, short, 10)
-            chain = None
-            if not grouped:
-                # the five-kernel chain with nothing flagged still enqueues its flag reduction and its
-                # (empty) recomputation launches: the fixed cost of the flag machinery
-                chain = round(wall(rm.step, short, 10) * 1e6, 2)
-            extras["overflow"] = {"rows_flagged": len(planted), "rows": B * Hq,
-                                  "chain_us_with": extras.get("multikernel_chain_us"), "chain_us_without": chain,
-                                  "us_with": round(t_with * 1e6, 2), "us_with_one_row": round(t_one * 1e6, 2),
-                                  "us_without": round(t_without * 1e6, 2),
-                                  "overhead_pct": round(100.0 * (t_with / t_without - 1.0), 2),
-                                  "overhead_one_row_pct": round(100.0 * (t_one / t_without - 1.0), 2)}
+        extras["hot_cache_us"] = us(timer(lambda i: run.step(0), repeats=3)["median"])
 
-    if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # the same step over a paged cache: every layer's K and V cut into pages that sit at
         # seeded-random places of a pool (fd_decode_attn_paged); pages of 16 and of 256 tokens
+        log("extras: paged cache, fused append")
+        gen = wl.gen
         paged, paged_append = {}, {}
         for page in (16, 256):
             if Smax % page or chunk > 64 * page:
@@ -406,12 +497,14 @@ def main():
             T = Smax // page
             perm = torch.randperm(B * T, generator=gen, device=dev)
             table = perm.view(B, T).to(torch.int32).contiguous()
+
             def pool(t):
                 pages = t.view(B, Hkv, T, page, D).permute(0, 2, 1, 3, 4).reshape(B * T, Hkv, page, D)
                 out_pool = torch.empty((B * T, Hkv, page, D), dtype=t.dtype, device=dev)     # contiguous, whatever `pages` is
                 out_pool[perm] = pages
                 return out_pool
             kps, vps = [pool(t) for t in ks], [pool(t) for t in vs]
+
             def step_paged(i):
                 l = i % layers
                 fdattn.fd_decode_attn_paged(run.shape, qs[l].data_ptr(), kps[l].data_ptr(), vps[l].data_ptr(), table.data_ptr(),
@@ -425,38 +518,43 @@ def main():
             if not torch.allclose(out.float(), ref.float(), rtol=0.0, atol=1e-3):
                 print("bench.py: paged result differs from the contiguous one", file=sys.stderr)
                 return 1
-            paged[str(page)] = round(wall(step_paged, short, 10) * 1e6, 2)
+            paged[str(page)] = us(timer(step_paged, repeats=3)["median"])
             # ... and with the cache update fused in (one key fewer resident; the rows go into their page)
             lens_p = torch.clamp(seq_lens - 1, min=0)
             kn_p = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
             vn_p = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+
             def step_paged_append(i):
                 l = i % layers
                 fdattn.fd_decode_attn_paged_append(run.shape, qs[l].data_ptr(), kn_p.data_ptr(), vn_p.data_ptr(), kps[l].data_ptr(),
                                                    vps[l].data_ptr(), table.data_ptr(), page, B * T, lens_p.data_ptr(), phi, bounds,
                                                    out.data_ptr(), run.ws.data_ptr(), run.ws_bytes, stream)
-            paged_append[str(page)] = round(wall(step_paged_append, short, 10) * 1e6, 2)
+            paged_append[str(page)] = us(timer(step_paged_append, repeats=3)["median"])
             del kps, vps
         extras["paged_us"] = paged
         extras["paged_append_us"] = paged_append
-
-    if not args.no_extras and entry in ("fd_decode_attn", "fd_decode_attn_gqa"):
         # the same step with the cache update fused in: one key fewer in the cache, the step's own
         # K/V rows attended from their buffers and stored by the same launch (last: it writes the caches)
         lens_m1 = torch.clamp(seq_lens - 1, min=0)
         k_new = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
         v_new = torch.randn((B, Hkv, D), generator=gen, device=dev, dtype=torch.float32).half()
+
         def append(i):
             l = i % layers
             fdattn.fd_decode_attn_append(run.shape, qs[l].data_ptr(), k_new.data_ptr(), v_new.data_ptr(), ks[l].data_ptr(),
                                          vs[l].data_ptr(), lens_m1.data_ptr(), phi, bounds, out.data_ptr(),
                                          run.ws.data_ptr(), run.ws_bytes, stream)
-        extras["fused_append_us"] = round(wall(append, short, 10) * 1e6, 2)
+        extras["fused_append_us"] = us(timer(append, repeats=3)["median"])
+        if wl.planted:
+            extras["overflow"] = overflow_ab(wl, timer, chunk)      # (last: it takes the planted keys out)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         # the oracle as it stands, on the host threads: whole layer-steps of layer 0, repeated
         # until about ten seconds of work are done
+        from oracle import fd_oracle
+        log("cpu baseline: the oracle on %d host threads, about 10 s" % ncpu)
+        case0, seq_lens_np = wl.case0, wl.seq_lens_np
         reps, t_total = 1, t_cpu
         while t_total < 10.0 and reps < 4096:
             t0 = time.perf_counter()
@@ -487,25 +585,70 @@ def main():
         "value": round(value, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 6),
-        "us_per_layer_step": round(sec_per_step * 1e6, 2),
+        "us_per_layer_step": us(sec_per_step),
+        "us_per_layer_step_min": us(t_call["min"]),
+        "us_per_layer_step_repeats": [us(x) for x in t_call["all"]],
+        "wall_us_per_layer_step": us(t_call["wall_median"]),
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
+        "pct_of_hbm_peak_best_repeat": round(100.0 * kv_bytes / t_call["min"] / 1e9 / HBM_PEAK_GBS, 2),
+        "timing": {"clock": "HIP events on the launch stream", "calls_per_repeat": t_call["calls"],
+                   "warmup_calls": t_call["warmup"], "repeats": t_call["repeats"], "reported": "median repeat",
+                   "note": "a --steps below 200 does not shorten the timed loop: each repeat is max(steps, 200) "
+                           "back-to-back calls, one step = one call"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": args.workload, "entry": entry, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
-                   "head_dim": D, "max_seq": Smax, "valid_keys": valid_keys, "chunk": chunk,
-                   "chunk_source": "--chunk" if args.chunk else ("workload definition" if chunk != picked or args.workload.startswith("c0")
+                   "head_dim": D, "max_seq": Smax, "valid_keys": wl.valid_keys, "chunk": chunk,
+                   "chunk_source": "--chunk" if args.chunk else ("workload definition" if args.workload.startswith("c0")
                                                                    else "fd_pick_chunk"),
                    "kv_bytes_per_step": kv_bytes, "layers_cycled": layers, "cache": "cold (rotating KV sets)",
-                   "phi": phi, "bounds": list(bounds), "kv_dtype": "f16",
-                   "launches_per_step": 1 if run.single_launch else (5 if entry == "fd_decode_attn_multikernel" else 2)},
+                   "phi": phi, "bounds": list(bounds), "kv_dtype": "f16", "accumulate_dtype": "f32",
+                   "launches_per_step": run.launches},
         "parity_max_abs_vs_oracle": max_abs, "parity_elements_beyond_1_fp16_ulp": beyond_1ulp,
-        "parity_elements": int(got.size),
+        "parity_elements": n_elements,
         "device": {"name": torch.cuda.get_device_name(dev),
                    "hbm_gib": round(torch.cuda.get_device_properties(dev).total_memory / 2**30, 1),
                    "compute_units": torch.cuda.get_device_properties(dev).multi_processor_count},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     line.update(extras)
+
+    if not args.no_workloads and args.entry == "auto" and not args.chunk:
+        # ---- the other workloads of the set, the overflow overhead and the prefill figure ----
+        del run, qs, ks, vs, wl
+        torch.cuda.empty_cache()
+        block = {}
+        for name in synth.CONFIGS:
+            if name == args.workload:
+                continue
+            log("workload %s" % name)
+            w = Workload(torch, np, fdattn, synth, name, 0, dev)
+            r = w.runner()
+            rec = workload_summary(w, r, timer, ncpu)
+            if not (rec["parity_max_abs_vs_oracle"] <= 2e-3):
+                print("bench.py: %s differs from the oracle (max-abs %.3e)" % (name, rec["parity_max_abs_vs_oracle"]), file=sys.stderr)
+                return 1
+            if w.planted:
+                log("overflow A/B on %s" % name)
+                rec["overflow"] = overflow_ab(w, timer, r.chunk)
+                line["fallback_overhead_pct_at_1pct_rows"] = rec["overflow"]["overhead_pct"]
+                line["fallback_overhead_pct_at_1pct_rows_chain"] = rec["overflow"]["chain_overhead_pct"]
+            block[name] = rec
+            del w, r
+            torch.cuda.empty_cache()
+        log("prefill, 8192 tokens")
+        try:
+            m = prefill_measure(torch, np, fdattn, synth, dev, 8192, 32, 32, timer)
+        except RuntimeError as e:
+            print("bench.py: %s" % e, file=sys.stderr)
+            return 1
+        block["prefill_b1_h32_s8192"] = {"entry": "fd_prefill_attn", "ms_per_call": round(m["t"]["median"] * 1e3, 4),
+                                         "ms_min": round(m["t"]["min"] * 1e3, 4),
+                                         "tflops": round(m["flops"] / m["t"]["median"] / 1e12, 1),
+                                         "frac_of_mfma_peak": round(m["flops"] / m["t"]["median"] / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                                         "parity_max_abs_vs_oracle": m["max_abs"], "parity_rows_sampled": m["rows"]}
+        line["workloads"] = block
+
     print(json.dumps(line))
     return 0
 

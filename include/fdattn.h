@@ -246,16 +246,19 @@ fd_status fd_decode_attn_paged_append(const fd_shape *shape, const void *q, cons
                                       void *out, fd_workspace ws, void *stream);
 
 /*
- * The same method as a chain of five small-step kernels with no atomics at all,
- * following Section 3 to the letter:
- *   1. per (row, chunk): Eq. 4 inner sums and the range guard;
- *   2. chunk flags -> row flags, ascending list and count of flagged rows;
- *   3. unflagged rows: Eq. 4 outer sums and the division;
- *   4. flagged rows only: EVERY chunk of the row recomputed by the synchronized
- *      partial softmax (m, l, f.V), work spread over the grid by (row, chunk);
- *   5. flagged rows only: the synchronized update of Eq. 2, written to out.
- * Needs no fd_workspace_init.  Five dependent launches cost about 12 us on an
- * MI355X regardless of size, which is why fd_decode_attn fuses them.
+ * The same method as a chain of three dependent launches with no atomics at all and no
+ * hand-over inside a launch, following Section 3 to the letter:
+ *   1. per (row, chunk): Eq. 4 inner sums and the range guard (partial sums, chunk flags);
+ *   2. per (row, chunk) again, once all partial vectors of launch 1 exist: the row flag =
+ *      OR of the row's chunk flags.  Unflagged rows: the workgroup of chunk 0 forms the
+ *      Eq. 4 outer sums and the division (atomic-free: one workgroup owns one output row,
+ *      fixed summation order).  Flagged rows: EVERY chunk of the row is recomputed by the
+ *      synchronized partial softmax (m, l, f.V) -- the whole vector, as the paper says;
+ *   3. flagged rows only: the synchronized update of Eq. 2 over the row's recomputed
+ *      partial vectors, written to out; one more workgroup turns the row flags into the
+ *      ascending list of flagged rows and their count.
+ * Needs no fd_workspace_init.  A launch that depends on the previous one starts about 3 us
+ * after it on an MI355X whatever its size, which is why fd_decode_attn fuses the three.
  * Fills chunk_flags, row_flags, n_flagged and flagged_rows.
  */
 fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const void *k_cache,

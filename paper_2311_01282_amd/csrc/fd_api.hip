@@ -473,10 +473,8 @@ fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const
     if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     FD_TRY(fd::launch_partial_unified(p, s));
-    FD_TRY(fd::launch_flag_reduce(p, s));
-    FD_TRY(fd::launch_combine_unified(p, s));
-    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/true, s));
-    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/true, s));
+    FD_TRY(fd::launch_chain_combine(p, s));
+    FD_TRY(fd::launch_chain_finish(p, s));
     return FD_OK;
 }
 
@@ -500,8 +498,8 @@ fd_status fd_decode_attn_sync(const fd_shape *shape, const void *q, const void *
     if (st != FD_OK) return st;
     if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    FD_TRY(fd::launch_partial_sync(p, /*use_list=*/false, s));
-    FD_TRY(fd::launch_combine_sync(p, /*use_list=*/false, s));
+    FD_TRY(fd::launch_partial_sync(p, s));
+    FD_TRY(fd::launch_combine_sync(p, s));
     return FD_OK;
 }
 

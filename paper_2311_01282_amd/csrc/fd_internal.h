@@ -95,11 +95,12 @@ inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStr
 // fd_row_kernels.hip : one query head per workgroup (VALU path)
 hipError_t launch_decode_fused(const Problem &p, hipStream_t s);
 hipError_t launch_partial_unified(const Problem &p, hipStream_t s);
-hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s);
-// fd_reduce_kernels.hip : flag reduction and the two combines
+hipError_t launch_chain_combine(const Problem &p, hipStream_t s);
+hipError_t launch_partial_sync(const Problem &p, hipStream_t s);
+// fd_reduce_kernels.hip : flag reduction, the synchronized merge, the chain's last launch, the row epilogue
 hipError_t launch_flag_reduce(const Problem &p, hipStream_t s);
-hipError_t launch_combine_unified(const Problem &p, hipStream_t s);
-hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s);
+hipError_t launch_chain_finish(const Problem &p, hipStream_t s);
+hipError_t launch_combine_sync(const Problem &p, hipStream_t s);
 hipError_t launch_clear_tickets(int32_t *ticket, size_t n, hipStream_t s);
 hipError_t launch_row_epilogue(const Problem &p, hipStream_t s);
 // fd_gqa_kernels.hip : one KV head (a group of query heads) per workgroup (MFMA path)

@@ -1,6 +1,6 @@
-// Small kernels of the multi-kernel chain: flag reduction, the outer sums of
-// Eq. 4 (atomic-free: one workgroup owns one output row), and the synchronized
-// merge of Eq. 2 for recomputed rows.  Plus the ticket clear of fd_workspace_init.
+// Small kernels: the flag reduction of fd_list_flagged_rows, the synchronized merge of
+// Eq. 2 (fd_decode_attn_sync; third launch of the literal chain), the row epilogue as a
+// launch of its own, and the counter clear of fd_workspace_init.
 #include "fd_chunk.h"
 
 namespace fd {
@@ -69,31 +69,56 @@ __global__ __launch_bounds__(1024) void flag_reduce_kernel(const Problem p)
     if (tid == 0) *p.ws.count = base_s;
 }
 
-// Eq. 4 outer accumulation and the division, for rows that raised no flag.
-__global__ __launch_bounds__(kHeadDim) void combine_unified_kernel(const Problem p)
+// Eq. 2: m = max_c m_c, result = sum_c e^{m_c - m} (f.V)_c / sum_c e^{m_c - m} l_c.
+__global__ __launch_bounds__(kHeadDim) void combine_sync_kernel(const Problem p)
 {
-    const int row = blockIdx.x, t = threadIdx.x;
-    if (p.ws.row_flags[row]) return;            // recomputed by the synchronized scheme
+    const int t = threadIdx.x;
+    const int row = blockIdx.x;
     const int S = valid_len(p, row / p.Hq);
     const int nb = (S + p.C - 1) / p.C;
     const float *num = p.ws.num + (size_t)row * p.nc * kHeadDim + t;
     const float *den = p.ws.den + (size_t)row * p.nc;
+    const float *mloc = p.ws.mloc + (size_t)row * p.nc;
+    float m = -INFINITY;
+    for (int c = 0; c < nb; ++c) m = fmaxf(m, mloc[c]);
     float s = 0.f, l = 0.f;
-#pragma unroll 8
+#pragma unroll 4
     for (int c = 0; c < nb; ++c) {
-        s += num[(size_t)c * kHeadDim];
-        l += den[c];
+        const float a = __builtin_amdgcn_exp2f((mloc[c] - m) * kLog2e);
+        s = __builtin_fmaf(a, num[(size_t)c * kHeadDim], s);
+        l = __builtin_fmaf(a, den[c], l);
     }
     p.out[(size_t)row * kHeadDim + t] = nb > 0 ? to_half_bits(s / l) : (uint16_t)0;
 }
 
-// Eq. 2: m = max_c m_c, result = sum_c e^{m_c - m} (f.V)_c / sum_c e^{m_c - m} l_c.
-__global__ __launch_bounds__(kHeadDim) void combine_sync_kernel(const Problem p, const int use_list)
+// Third launch of the literal chain.  Blocks 0 .. gridDim.x - 2 stride over the rows and finish the
+// flagged ones: Eq. 2 over the row's recomputed partial vectors, m = max_c m_c, result =
+// sum_c e^{m_c - m} (f.V)_c / sum_c e^{m_c - m} l_c.  The last block turns the row flags into the
+// ascending list of flagged rows and their count (prefix sums over ballots, no atomics).
+__global__ __launch_bounds__(kHeadDim) void chain_finish_kernel(const Problem p)
 {
     const int t = threadIdx.x;
-    const int n = use_list ? *p.ws.count : p.rows;
-    for (int i = blockIdx.x; i < n; i += gridDim.x) {
-        const int row = use_list ? p.ws.list[i] : i;
+    const int workers = (int)gridDim.x - 1;
+    if ((int)blockIdx.x == workers) {
+        __shared__ int cnt[2];
+        const int lane = t & 63, wave = t >> 6;
+        int base = 0;
+        for (int r0 = 0; r0 < p.rows; r0 += kHeadDim) {
+            const int row = r0 + t;
+            const int f = row < p.rows ? (int)p.ws.row_flags[row] : 0;
+            const unsigned long long mask = __ballot(f);
+            if (lane == 0) cnt[wave] = __popcll(mask);
+            __syncthreads();
+            const int before = (wave ? cnt[0] : 0) + __popcll(mask & ((1ull << lane) - 1ull));
+            if (f) p.ws.list[base + before] = row;
+            base += cnt[0] + cnt[1];
+            __syncthreads();
+        }
+        if (t == 0) *p.ws.count = base;
+        return;
+    }
+    for (int row = blockIdx.x; row < p.rows; row += workers) {
+        if (!p.ws.row_flags[row]) continue;
         const int S = valid_len(p, row / p.Hq);
         const int nb = (S + p.C - 1) / p.C;
         const float *num = p.ws.num + (size_t)row * p.nc * kHeadDim + t;
@@ -133,17 +158,16 @@ hipError_t launch_flag_reduce(const Problem &p, hipStream_t s)
     return launch(flag_reduce_kernel, dim3(1), dim3(1024), s, p);
 }
 
-hipError_t launch_combine_unified(const Problem &p, hipStream_t s)
+hipError_t launch_chain_finish(const Problem &p, hipStream_t s)
 {
     if (p.rows == 0) return hipSuccess;
-    return launch(combine_unified_kernel, dim3(p.rows), dim3(kHeadDim), s, p);
+    return launch(chain_finish_kernel, dim3((p.rows < 1024 ? p.rows : 1024) + 1), dim3(kHeadDim), s, p);
 }
 
-hipError_t launch_combine_sync(const Problem &p, bool use_list, hipStream_t s)
+hipError_t launch_combine_sync(const Problem &p, hipStream_t s)
 {
     if (p.rows == 0) return hipSuccess;
-    const int grid = use_list ? (p.rows < 512 ? p.rows : 512) : p.rows;
-    return launch(combine_sync_kernel, dim3(grid), dim3(kHeadDim), s, p, use_list ? 1 : 0);
+    return launch(combine_sync_kernel, dim3(p.rows), dim3(kHeadDim), s, p);
 }
 
 }  // namespace fd

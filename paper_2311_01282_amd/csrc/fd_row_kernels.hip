@@ -7,9 +7,10 @@
 //       guard fired is recomputed on the spot with its own maximum (Eq. 2); the
 //       workgroup that finishes a row last (elected by a small tree of arrival
 //       counters) runs the row epilogue.
-//   partial_unified_kernel : Eq. 4 inner sums + guard only (multi-kernel chain).
-//   partial_sync_kernel    : per-chunk part of the synchronized scheme, for all
-//       rows or for the listed (flagged) rows only.
+//   partial_unified_kernel : Eq. 4 inner sums + guard only (first launch of the chain).
+//   chain_combine_kernel   : row flags; Eq. 4 outer sums for clean rows, per-chunk
+//       synchronized recomputation for flagged rows (second launch of the chain).
+//   partial_sync_kernel    : per-chunk part of the synchronized scheme, for all rows.
 #include "fd_chunk.h"
 
 namespace fd {
@@ -92,34 +93,89 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     else row_epilogue<NW, true>(p, row, nb, [nb] { return nb; }, &lds.acc[0][0]);
 }
 
-template <int C>
-__global__ __launch_bounds__(256) void partial_unified_kernel(const Problem p)
+// First launch of the literal chain: Eq. 4 inner sums and the range guard, nothing else (no
+// recomputation, no hand-over).  Same workgroup shape, workgroup order and early loads as the
+// fused kernel: SMALL = a launch of at most 1024 workgroups (chunk-major order), EARLY = of at
+// most 256 (first loads before the sequence length has arrived).
+template <int C, bool SMALL, bool EARLY>
+__global__ __launch_bounds__(Tune<C>::NW * 64) void partial_unified_kernel(const Problem p)
 {
-    __shared__ ChunkLds<4, 1> lds;
-    const int w = blockIdx.x;
-    chunk_body<C, 4, (C / 16 < 4 ? C / 16 : 4), false>(p, w / p.nc, w % p.nc, lds);
+    static_assert(!EARLY || SMALL, "early loads belong to the small launches");
+    constexpr int NW = Tune<C>::NW, UP = Tune<C>::UP;
+    __shared__ ChunkLds<NW, 1> lds;
+    if constexpr (SMALL) fetch_arguments_now(p);
+    const int groups8 = (p.rows + 7) >> 3;
+    const int j = blockIdx.x >> 3;
+    const int c = SMALL ? j / groups8 : j % p.nc;
+    const int row = (blockIdx.x & 7) + 8 * (SMALL ? j - c * groups8 : j / p.nc);
+    if (row >= p.rows) return;
+    chunk_body<C, NW, UP, false, 1, EARLY, false>(p, row, c, lds);
 }
 
-// use_list == false: every (row, chunk), one per workgroup.
-// use_list == true : only the rows in ws.list[0 .. *ws.count); the grid is fixed
-// and workgroups stride over (flagged row, chunk) items, so the launch needs no
-// host knowledge of the count and exits at once when nothing is flagged.
+// Second launch of the literal chain, over (row, chunk) items: every item first forms its row's
+// flag, the OR of the row's chunk flags (Section 3 "Recomputation": one logit out of range
+// condemns the whole vector).
+//   row clean   : the item of chunk 0 adds the row's partial sums and divides -- Eq. 4 outer
+//                 sums, fixed order, no atomics; the other items have nothing to do;
+//   row flagged : every item recomputes its chunk by the synchronized partial softmax -- chunk
+//                 maximum m, l = sum e^{x-m}, f.V -- into the chunk's slot (Eq. 2, per partial
+//                 vector); the third launch merges them.
+// The grid is bounded; workgroups stride over the items.
+template <int C> struct ChainTune {
+    static constexpr int NW = 8;
+    static constexpr int NG = C / (4 * NW);
+    static constexpr int UP = NG < 8 ? NG : 8;
+};
 template <int C>
-__global__ __launch_bounds__(256) void partial_sync_kernel(const Problem p, const int use_list)
+__global__ __launch_bounds__(ChainTune<C>::NW * 64) void chain_combine_kernel(const Problem p)
+{
+    constexpr int NW = ChainTune<C>::NW, UP = ChainTune<C>::UP, NT = NW * 64;
+    __shared__ ChunkLds<NW, C> lds;
+    const int tid = threadIdx.x;
+    const long long items = (long long)p.rows * p.nc;
+    for (long long w = blockIdx.x; w < items; w += gridDim.x) {
+        const int row = (int)(w / p.nc), c = (int)(w % p.nc);
+        const int S = valid_len(p, row / p.Hq);
+        const int nb = (S + p.C - 1) / p.C;
+        const uint8_t *cf = p.ws.chunk_flags + (size_t)row * p.nc;
+        int f = 0;
+        for (int i = tid; i < nb; i += NT) f |= cf[i];
+        const int flagged = __syncthreads_or(f);
+        if (c == 0 && tid == 0) p.ws.row_flags[row] = flagged ? 1 : 0;
+        if (flagged) {
+            if (c < nb) chunk_body<C, NW, UP, true>(p, row, c, lds);
+        } else if (c == 0) {
+            // 4 slices of 128 threads; slice k adds chunks k, k+4, ...; the slices are added in order
+            const int slice = tid >> 7, t = tid & 127;
+            const float *num = p.ws.num + (size_t)row * p.nc * kHeadDim + t;
+            const float *den = p.ws.den + (size_t)row * p.nc;
+            float s = 0.f, l = 0.f;
+#pragma unroll 4
+            for (int i = slice; i < nb; i += 4) {
+                s += num[(size_t)i * kHeadDim];
+                l += den[i];
+            }
+            lds.acc[slice][t] = s;
+            if (t == 0) lds.den[slice] = l;
+            __syncthreads();
+            if (tid < kHeadDim) {
+                const float st = ((lds.acc[0][t] + lds.acc[1][t]) + lds.acc[2][t]) + lds.acc[3][t];
+                const float lt = ((lds.den[0] + lds.den[1]) + lds.den[2]) + lds.den[3];
+                p.out[(size_t)row * kHeadDim + t] = nb > 0 ? to_half_bits(st / lt) : (uint16_t)0;
+            }
+        }
+        __syncthreads();                        // lds is reused by the next item
+    }
+}
+
+// The synchronized partial softmax of every (row, chunk), one per workgroup (fd_decode_attn_sync).
+template <int C>
+__global__ __launch_bounds__(256) void partial_sync_kernel(const Problem p)
 {
     constexpr int UP = C / 16 < 8 ? C / 16 : 8;
     __shared__ ChunkLds<4, C> lds;
-    if (!use_list) {
-        const int w = blockIdx.x;
-        chunk_body<C, 4, UP, true>(p, w / p.nc, w % p.nc, lds);
-        return;
-    }
-    const long long items = (long long)(*p.ws.count) * p.nc;
-    for (long long w = blockIdx.x; w < items; w += gridDim.x) {
-        const int row = p.ws.list[w / p.nc];
-        chunk_body<C, 4, UP, true>(p, row, (int)(w % p.nc), lds);
-        __syncthreads();                        // lds is reused by the next item
-    }
+    const int w = blockIdx.x;
+    chunk_body<C, 4, UP, true>(p, w / p.nc, w % p.nc, lds);
 }
 
 template <template <int> class Launcher, typename... Args>
@@ -157,20 +213,32 @@ template <int C> struct FusedLauncher {
 template <int C> struct UnifiedLauncher {
     static hipError_t run(const Problem &p, hipStream_t s)
     {
-        const unsigned grid = (unsigned)((long long)p.rows * p.nc);
+        const unsigned grid = (unsigned)(8ll * ((p.rows + 7) / 8) * p.nc);
         if (grid == 0) return hipSuccess;
-        return launch(partial_unified_kernel<C>, dim3(grid), dim3(256), s, p);
+        const dim3 block(Tune<C>::NW * 64);
+        if (grid <= (unsigned)kComputeUnits) return launch(partial_unified_kernel<C, true, true>, dim3(grid), block, s, p);
+        if (grid <= 1024u) return launch(partial_unified_kernel<C, true, false>, dim3(grid), block, s, p);
+        return launch(partial_unified_kernel<C, false, false>, dim3(grid), block, s, p);
+    }
+};
+
+template <int C> struct ChainCombineLauncher {
+    static hipError_t run(const Problem &p, hipStream_t s)
+    {
+        const long long items = (long long)p.rows * p.nc;
+        if (items == 0) return hipSuccess;
+        // two workgroups of 8 wavefronts fit a compute unit: a few rounds' worth, striding over the items
+        const unsigned grid = (unsigned)(items < 2048 ? items : 2048);
+        return launch(chain_combine_kernel<C>, dim3(grid), dim3(ChainTune<C>::NW * 64), s, p);
     }
 };
 
 template <int C> struct SyncLauncher {
-    static hipError_t run(const Problem &p, bool use_list, hipStream_t s)
+    static hipError_t run(const Problem &p, hipStream_t s)
     {
         const long long all = (long long)p.rows * p.nc;
         if (all == 0) return hipSuccess;
-        const long long cap = 4096;             // resident capacity is 256 CUs x a few workgroups
-        const unsigned grid = (unsigned)(use_list ? (all < cap ? all : cap) : all);
-        return launch(partial_sync_kernel<C>, dim3(grid), dim3(256), s, p, use_list ? 1 : 0);
+        return launch(partial_sync_kernel<C>, dim3((unsigned)all), dim3(256), s, p);
     }
 };
 
@@ -186,9 +254,14 @@ hipError_t launch_partial_unified(const Problem &p, hipStream_t s)
     return dispatch_chunk<UnifiedLauncher>(chunk_capacity(p.C), p, s);
 }
 
-hipError_t launch_partial_sync(const Problem &p, bool use_list, hipStream_t s)
+hipError_t launch_chain_combine(const Problem &p, hipStream_t s)
 {
-    return dispatch_chunk<SyncLauncher>(chunk_capacity(p.C), p, use_list, s);
+    return dispatch_chunk<ChainCombineLauncher>(chunk_capacity(p.C), p, s);
+}
+
+hipError_t launch_partial_sync(const Problem &p, hipStream_t s)
+{
+    return dispatch_chunk<SyncLauncher>(chunk_capacity(p.C), p, s);
 }
 
 }  // namespace fd

@@ -52,7 +52,8 @@ def parse():
     ap.add_argument("--chunk", type=int, default=0, help="0 = the workload's default")
     ap.add_argument("--layers", type=int, default=0, help="distinct KV caches to cycle through (0 = auto)")
     ap.add_argument("--entry", default="auto", choices=["auto", "fd_decode_attn", "fd_decode_attn_gqa",
-                                                        "fd_decode_attn_multikernel", "fd_decode_attn_sync"])
+                                                        "fd_decode_attn_multikernel", "fd_decode_attn_sync",
+                                                        "fd_decode_attn_static"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip chunk sweep, sync baseline, paged / append variants")
     ap.add_argument("--no-workloads", action="store_true", help="skip the block with the other workloads, overflow and prefill")
@@ -192,13 +193,13 @@ class Runner:
         self.ws_bytes = fdattn.fd_workspace_bytes(self.shape)
         self.ws = wl.torch.empty(self.ws_bytes, dtype=wl.torch.uint8, device=wl.dev)
         fdattn.fd_workspace_init(self.shape, self.ws.data_ptr(), self.ws_bytes, wl.stream)
-        gqa = entry == "fd_decode_attn_gqa"
+        gqa = entry == "fd_decode_attn_gqa" or (entry == "fd_decode_attn_static" and wl.grouped)
         self.gqa = gqa
         nc = -(-wl.Smax // chunk)
         wgs = wl.B * (wl.Hkv if gqa else wl.Hq) * nc
         # the library's own rule: the grouped kernel finishes its rows itself up to 256 workgroups and 8 chunks
         # per row, the per-row kernel up to 1024 workgroups; beyond, the row epilogue is a launch of its own
-        fused = entry in ("fd_decode_attn", "fd_decode_attn_gqa")
+        fused = entry in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_static")
         self.single_launch = fused and ((wgs <= 256 and nc <= 8) if gqa else wgs <= 1024)
         self.launches = 1 if self.single_launch else (3 if entry == "fd_decode_attn_multikernel" else 2)
         self.grid = (wl.B * wl.Hkv * nc) if gqa else 8 * ((wl.B * wl.Hq + 7) // 8) * nc
@@ -221,6 +222,8 @@ class Runner:
         a = (self.shape, wl.qs[l].data_ptr(), wl.ks[l].data_ptr(), wl.vs[l].data_ptr(), wl.seq_lens.data_ptr())
         if self.entry == "fd_decode_attn_sync":
             fdattn.fd_decode_attn_sync(*a, wl.out.data_ptr(), self.ws.data_ptr(), self.ws_bytes, wl.stream)
+        elif self.entry == "fd_decode_attn_static":
+            fdattn.fd_decode_attn_static(*a, wl.synth.PHI, wl.synth.BOUNDS, wl.out.data_ptr(), wl.stream)
         else:
             getattr(fdattn, self.entry)(*a, wl.synth.PHI, wl.synth.BOUNDS, wl.out.data_ptr(), self.ws.data_ptr(),
                                         self.ws_bytes, wl.stream)
@@ -407,7 +410,7 @@ def main():
 
     # ---- dominant kernel: the chunk kernel (the whole call when it is a single launch) ----
     roofline = None
-    fused_entries = ("fd_decode_attn", "fd_decode_attn_gqa")
+    fused_entries = ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_static")
     if entry in fused_entries:
         t_k = t_call if run.single_launch else timer(run.chunk_kernel)
         k_sec = t_k["median"]
@@ -452,6 +455,9 @@ def main():
         extras["sync_baseline_us"] = us(timer(wl.runner(chunk, "fd_decode_attn_sync").step, repeats=3)["median"])
         if not wl.grouped:
             extras["multikernel_chain_us"] = us(timer(wl.runner(chunk, "fd_decode_attn_multikernel").step, repeats=3)["median"])
+        # the entry point that allocates nothing (its workspace is a device array inside the library)
+        if run.ws_bytes <= fdattn.FD_STATIC_SCRATCH_BYTES:
+            extras["static_entry_us"] = us(timer(wl.runner(chunk, "fd_decode_attn_static").step, repeats=3)["median"])
         # statistics pass of the calibration (reads K only): histogram of the scaled logits
         n_bins = 256
         hist = torch.zeros(n_bins + 2, dtype=torch.int64, device=dev)

@@ -68,7 +68,8 @@ typedef enum {
     FD_ERR_BOUNDS = 3,       /* lo >= hi, or phi / a bound is NaN or infinite   */
     FD_ERR_WORKSPACE = 4,    /* workspace NULL, misaligned or too small         */
     FD_ERR_UNSUPPORTED = 5,  /* valid in principle, not built (head_dim, chunk) */
-    FD_ERR_HIP = 6           /* the HIP runtime refused a launch                */
+    FD_ERR_HIP = 6,          /* the HIP runtime refused a launch                */
+    FD_ERR_STATIC_LIMIT = 7  /* fd_decode_attn_static: shape beyond its scratch */
 } fd_status;
 
 /* Problem shape.  Plain data, read during the call only. */
@@ -244,6 +245,40 @@ fd_status fd_decode_attn_paged_append(const fd_shape *shape, const void *q, cons
                                       void *k_pool, void *v_pool, const int32_t *block_table, int32_t page_size,
                                       int32_t n_pages, const int32_t *seq_lens, float phi, fd_bounds bounds,
                                       void *out, fd_workspace ws, void *stream);
+
+/*
+ * fd_decode_attn / fd_decode_attn_gqa for callers that cannot allocate or carry a
+ * workspace: code recorded by a stream capture that must not call hipMalloc, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments minus `ws`; same
+ * kernels, same results bit for bit (grouped shapes, 2 <= n_q_heads / n_kv_heads <=
+ * 16, take the grouped kernel, all others the per-row kernel).  The partial results,
+ * flags and arrival counters live in a device array that is part of the library's
+ * code object: FD_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the
+ * process ends.  The call allocates nothing and frees nothing (no hipMalloc, no
+ * hipFree, no allocating runtime or library routine); the caller still owns q, the
+ * caches, seq_lens and out.
+ *   Limit.  fd_workspace_bytes(shape) <= FD_STATIC_SCRATCH_BYTES, else
+ *     FD_ERR_STATIC_LIMIT before anything is enqueued (8 MiB hold about 14 000
+ *     (row, chunk) slots: every workload shape of this repository at its picked
+ *     chunk size; e.g. 32 rows x 8 chunks need 0.15 MiB, 128 rows x 32 chunks 2.3 MiB).
+ *   Device.  The array of the CURRENT device is used (hipGetDevice at the call);
+ *     `stream` must belong to it.  The first call on each device looks the array's
+ *     address up and enqueues one clear of its arrival counters on `stream`; make that
+ *     first call outside a stream capture.
+ *   Sharing.  Every call on a GPU uses that GPU's one array, which keeps the last
+ *     call's partial results and flags (nothing of them is an input of the next call;
+ *     the arrival counters are zero between completed calls).  Calls that may overlap
+ *     on one GPU -- different streams, different host threads -- RACE on it: use
+ *     fd_decode_attn with distinct workspaces for those.  There is no fd_get_flags for
+ *     the static array; callers that need flags use the workspace form.
+ *   After a call that did not complete (see fd_workspace_init) the process has lost its
+ *     device context anyway; there is nothing to re-initialise.
+ * Other errors as fd_decode_attn; FD_ERR_HIP also when the array's address cannot be
+ * obtained or the current device's ordinal is 64 or more.
+ */
+#define FD_STATIC_SCRATCH_BYTES (8u << 20)
+fd_status fd_decode_attn_static(const fd_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *seq_lens, float phi, fd_bounds bounds, void *out, void *stream);
 
 /*
  * The same method as a chain of three dependent launches with no atomics at all and no

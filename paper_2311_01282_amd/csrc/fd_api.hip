@@ -4,6 +4,7 @@
 
 #include <cfloat>
 #include <cmath>
+#include <mutex>
 
 namespace {
 
@@ -461,6 +462,69 @@ fd_status fd_decode_attn_paged_append(const fd_shape *shape, const void *q, cons
     return run_fused(p, static_cast<hipStream_t>(stream));
 }
 
+// ---- fd_decode_attn_static: the workspace lives in the library's own device memory ----
+//
+// `static_scratch` is the array's host-side stand-in: in host code the name is not a device
+// address.  The address on the current device comes from hipGetSymbolAddress, once per device
+// (every GPU holds its own copy of the array at its own address), and only that pointer is
+// handed to kernels.
+static __device__ __align__(256) unsigned char static_scratch[FD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void *g_static_ptr[kMaxDevices] = {};
+
+// Device address of static_scratch on the current device.  First call on a device: looks the
+// address up and enqueues one clear of the arrival-counter region on `s` (the array starts
+// zeroed with the code object; the clear makes the precondition explicit).  Allocates nothing.
+fd_status static_scratch_on_current_device(hipStream_t s, void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FD_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(static_scratch)) != hipSuccess || !ptr) return FD_ERR_HIP;
+        if (((uintptr_t)ptr % kAlign) != 0) return FD_ERR_HIP;
+        const fd_workspace ws{ptr, (size_t)FD_STATIC_SCRATCH_BYTES};
+        const size_t bytes = max_ticket_bytes(ws.bytes);
+        if (fd::launch_clear_tickets(reinterpret_cast<int32_t *>(ws_end(ws) - bytes), bytes / sizeof(int32_t), s) != hipSuccess)
+            return FD_ERR_HIP;
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return FD_OK;
+}
+}  // namespace
+
+fd_status fd_decode_attn_static(const fd_shape *shape, const void *q, const void *k_cache, const void *v_cache,
+                                const int32_t *seq_lens, float phi, fd_bounds bounds, void *out, void *stream)
+{
+    Layout L;
+    fd_status st = plan(shape, &L);
+    if (st != FD_OK) return st;
+    if (L.total > (size_t)FD_STATIC_SCRATCH_BYTES) return FD_ERR_STATIC_LIMIT;
+    // every host-side check comes before the first touch of the device
+    if (!q || !k_cache || !v_cache || !seq_lens || !out) return FD_ERR_NULL;
+    if (misaligned(q) || misaligned(k_cache) || misaligned(v_cache) || misaligned(out) || ((uintptr_t)seq_lens % 4) != 0)
+        return FD_ERR_SHAPE;
+    if (!std::isfinite(phi) || !std::isfinite(bounds.lo) || !std::isfinite(bounds.hi) || !(bounds.lo < bounds.hi))
+        return FD_ERR_BOUNDS;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void *ptr = nullptr;
+    st = static_scratch_on_current_device(s, &ptr);
+    if (st != FD_OK) return st;
+    const fd_workspace ws{ptr, (size_t)FD_STATIC_SCRATCH_BYTES};
+    fd::Problem p;
+    st = make_problem(shape, q, k_cache, v_cache, seq_lens, out, true, ws, &p);
+    if (st != FD_OK) return st;
+    st = set_guard(&p, phi, bounds);
+    if (st != FD_OK) return st;
+    if (p.rows == 0) return FD_OK;
+    return run_fused(p, s);
+}
+
 fd_status fd_decode_attn_multikernel(const fd_shape *shape, const void *q, const void *k_cache,
                                      const void *v_cache, const int32_t *seq_lens, float phi,
                                      fd_bounds bounds, void *out, fd_workspace ws, void *stream)
@@ -692,6 +756,9 @@ const char *fd_status_str(fd_status status)
         case FD_ERR_WORKSPACE: return "FD_ERR_WORKSPACE: workspace NULL, misaligned or too small";
         case FD_ERR_UNSUPPORTED: return "FD_ERR_UNSUPPORTED: shape not supported by this build";
         case FD_ERR_HIP: return "FD_ERR_HIP: the HIP runtime refused a launch";
+        case FD_ERR_STATIC_LIMIT:
+            return "FD_ERR_STATIC_LIMIT: the shape needs more scratch than fd_decode_attn_static holds "
+                   "(fd_workspace_bytes(shape) > FD_STATIC_SCRATCH_BYTES); use fd_decode_attn with a workspace";
     }
     return "unknown fd_status";
 }

@@ -18,7 +18,8 @@ if not os.path.exists(LIB_PATH):
 
 _lib = ctypes.CDLL(LIB_PATH)
 
-FD_OK, FD_ERR_NULL, FD_ERR_SHAPE, FD_ERR_BOUNDS, FD_ERR_WORKSPACE, FD_ERR_UNSUPPORTED, FD_ERR_HIP = range(7)
+FD_OK, FD_ERR_NULL, FD_ERR_SHAPE, FD_ERR_BOUNDS, FD_ERR_WORKSPACE, FD_ERR_UNSUPPORTED, FD_ERR_HIP, FD_ERR_STATIC_LIMIT = range(8)
+FD_STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class Shape(ctypes.Structure):
@@ -56,6 +57,8 @@ _lib.fd_status_str.argtypes = [ctypes.c_int]
 for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel"):
     getattr(_lib, _name).restype = ctypes.c_int
     getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+_lib.fd_decode_attn_static.restype = ctypes.c_int
+_lib.fd_decode_attn_static.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, _vp]
 _lib.fd_decode_attn_sync.restype = ctypes.c_int
 _lib.fd_decode_attn_sync.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, Workspace, _vp]
 for _name in ("fd_decode_attn_partial", "fd_decode_attn_gqa_partial"):
@@ -97,7 +100,7 @@ _lib.fd_prefill_attn.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Works
 _lib.fd_prefill_get_flags.restype = ctypes.c_int
 _lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
 
-EXPORTS = ("fd_decode_attn_paged", "fd_decode_attn_paged_append", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
+EXPORTS = ("fd_decode_attn_static", "fd_decode_attn_paged", "fd_decode_attn_paged_append", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",
            "fd_decode_attn_partial", "fd_decode_attn_gqa_partial", "fd_get_flags", "fd_get_partials",
            "fd_status_str")
@@ -133,6 +136,11 @@ def fd_decode_attn(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_pt
 def fd_decode_attn_gqa(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):
     _check(_lib.fd_decode_attn_gqa(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
                                    Bounds(*bounds), out, Workspace(ws_ptr, ws_bytes), stream))
+
+
+def fd_decode_attn_static(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, stream=0):
+    _check(_lib.fd_decode_attn_static(ctypes.byref(shape), q, k_cache, v_cache, seq_lens, phi,
+                                      Bounds(*bounds), out, stream))
 
 
 def fd_decode_attn_multikernel(shape, q, k_cache, v_cache, seq_lens, phi, bounds, out, ws_ptr, ws_bytes, stream=0):

@@ -126,6 +126,39 @@ def test_bad_arguments_are_rejected_before_any_launch(fdattn, name):
         assert call(fdattn, name, good, ptrs[:4] + (0,)) == fdattn.FD_ERR_NULL               # out
 
 
+def test_static_entry_point_rejects_on_the_host(fdattn):
+    """fd_decode_attn_static: every host-visible problem, its size limit included, is reported before the
+    device is touched (there is none here)."""
+    ptrs = (0x10000, 0x20000, 0x30000, 0x40000, 0x50000)
+    def go(shape, p=ptrs, phi=3.0, bounds=(-60.0, 20.0)):
+        try:
+            fdattn.fd_decode_attn_static(shape, p[0], p[1], p[2], p[3], phi, bounds, p[4])
+        except fdattn.FdError as e:
+            return e.status
+        return fdattn.FD_OK
+    good = fdattn.make_shape(1, 4, 4, 128, 1024, 256, 0.0884)
+    assert go(good, (0,) + ptrs[1:]) == fdattn.FD_ERR_NULL
+    assert go(good, ptrs[:4] + (0,)) == fdattn.FD_ERR_NULL
+    assert go(good, (0x10008,) + ptrs[1:]) == fdattn.FD_ERR_SHAPE
+    assert go(good, bounds=(5.0, 5.0)) == fdattn.FD_ERR_BOUNDS
+    assert go(good, phi=float("nan")) == fdattn.FD_ERR_BOUNDS
+    assert go(fdattn.make_shape(1, 4, 4, 64, 1024, 256, 0.0884)) == fdattn.FD_ERR_UNSUPPORTED
+    assert go(fdattn.make_shape(1, 5, 2, 128, 1024, 256, 0.0884)) == fdattn.FD_ERR_SHAPE
+    # the limit: the shape's workspace must fit the library's static array
+    too_big = fdattn.make_shape(64, 32, 32, 128, 32768, 64, 0.0884)
+    assert fdattn.fd_workspace_bytes(too_big) > fdattn.FD_STATIC_SCRATCH_BYTES
+    assert go(too_big) == fdattn.FD_ERR_STATIC_LIMIT
+    assert "FD_STATIC_SCRATCH_BYTES" in fdattn.status_str(fdattn.FD_ERR_STATIC_LIMIT)
+    text = open(HEADER).read()
+    assert re.search(r"#define\s+FD_STATIC_SCRATCH_BYTES\s+\(8u << 20\)", text) and fdattn.FD_STATIC_SCRATCH_BYTES == 8 << 20
+    # the benchmark workloads fit at their picked chunk sizes
+    from paper_2311_01282_amd import synth
+    for name, cfg in synth.CONFIGS.items():
+        sh = fdattn.make_shape(cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"], 0, 0.1)
+        sh.chunk = cfg["chunk"] if name.startswith("c0") else fdattn.fd_pick_chunk(sh)
+        assert 0 < fdattn.fd_workspace_bytes(sh) <= fdattn.FD_STATIC_SCRATCH_BYTES, name
+
+
 def test_gqa_entry_point_needs_a_group(fdattn):
     ptrs = (0x10000, 0x20000, 0x30000, 0x40000, 0x50000)
     ungrouped = fdattn.make_shape(1, 4, 4, 128, 1024, 256, 0.0884)
@@ -143,7 +176,7 @@ def test_an_empty_batch_is_a_no_op(fdattn):
 
 
 def test_status_strings_and_getters(fdattn):
-    for code in range(7):
+    for code in range(8):
         assert fdattn.status_str(code).startswith("FD_")
     assert "unknown" in fdattn.status_str(99)
     sh = fdattn.make_shape(1, 4, 4, 128, 1024, 256, 0.0884)

@@ -46,6 +46,26 @@ def _link(lib, objs):
     os.replace(tmp, lib)
 
 
+# the phase-probe variant of the library (per-phase device timestamps in the per-row fused kernel;
+# see paper_2311_01282_amd/phase_probe.py): same sources, -DFD_PHASE_PROBE, objects of its own
+PHASE_LIB = os.path.join(HERE, "libfdattn_phase.so")
+
+
+def build_phase_probe(verbose=False):
+    os.makedirs(BUILD, exist_ok=True)
+
+    def one(src):
+        obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".phase.o")
+        subprocess.check_call([hipcc()] + FLAGS + ["-DFD_PHASE_PROBE", "-c", os.path.join(CSRC, src), "-o", obj])
+        return obj
+    with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
+        objs = list(ex.map(one, SOURCES))
+    _link(PHASE_LIB, objs)
+    if verbose:
+        print("built", PHASE_LIB)
+    return PHASE_LIB
+
+
 def build(extra_flags=(), verbose=False):
     os.makedirs(BUILD, exist_ok=True)
     with concurrent.futures.ThreadPoolExecutor(max_workers=4) as ex:
@@ -58,4 +78,7 @@ def build(extra_flags=(), verbose=False):
 
 
 if __name__ == "__main__":
-    build(extra_flags=sys.argv[1:], verbose=True)
+    if sys.argv[1:] == ["--phase-probe"]:
+        build_phase_probe(verbose=True)
+    else:
+        build(extra_flags=sys.argv[1:], verbose=True)

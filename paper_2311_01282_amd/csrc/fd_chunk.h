@@ -20,6 +20,26 @@
 
 namespace fd {
 
+// Phase probe (a build of its own, -DFD_PHASE_PROBE, never the product library): thread 0 of
+// every workgroup of the per-row fused kernel stamps the device's constant-rate clock (100 MHz)
+// at fixed points into a log that fd_phase_probe_read copies out.  Slots: 0 kernel entered,
+// 1 first block's data used, 2 chunk loop done, 3 workgroup's sums reduced and stores issued,
+// 4 stores performed, 5 arrival counted, 6 (finisher) partial results loaded and merged, 7
+// (finisher) output stored and performed.
+#ifdef FD_PHASE_PROBE
+constexpr int kPhaseSlots = 8, kPhaseMaxGrid = 4096;
+static __device__ unsigned long long fd_phase_log[kPhaseMaxGrid * kPhaseSlots];
+#define FD_PHASE(i)                                                                                         \
+    do {                                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        if (threadIdx.x == 0 && blockIdx.x < (unsigned)kPhaseMaxGrid)                                       \
+            fd_phase_log[(size_t)blockIdx.x * kPhaseSlots + (i)] = wall_clock64();                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
+    } while (0)
+#else
+#define FD_PHASE(i) do { } while (0)
+#endif
+
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -328,6 +348,17 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
 #pragma unroll
             for (int u = 0; u < UP; ++u)
                 if (key_of(u) > last) vA[u] = u32x4{0u, 0u, 0u, 0u};   // padding may hold anything
+#ifdef FD_PHASE_PROBE
+            // (probe build only: the first block peeled so that its arrival can be stamped)
+            if (blk + 2 < nblk) {
+                reduce(blk, kA, vA);
+                FD_PHASE(1);
+                issue(blk + 2, kA, vA);
+                reduce(blk + 1, kB, vB);
+                issue(blk + 3, kB, vB);
+                blk += 2;
+            }
+#endif
 #pragma unroll 1
             for (; blk + 2 < nblk; blk += 2) {
                 reduce(blk, kA, vA);
@@ -434,6 +465,7 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         }
     }
 
+    if constexpr (!SYNC) FD_PHASE(2);
     // Workgroup reduction: NW*4 partial vectors (NW wavefronts x 4 keys per group).
     // LDS row layout: elements 8s..8s+3 at 4s, elements 8s+4..8s+7 at 64 + 4((s + 4) & 15). Both the
     // 16-byte writes here and the 4-byte reads below then touch every bank once per pass.
@@ -581,6 +613,7 @@ __device__ __forceinline__ void row_epilogue(const Problem &p, int row, int n_lo
         if (t4 == 0) { L[slice] = l; M[slice] = m; }
     }
     const int rf = __syncthreads_or(f);
+    FD_PHASE(6);
     if (tid < 32) {
         float mm = M[0];
 #pragma unroll
@@ -684,6 +717,7 @@ __device__ __forceinline__ void rows_epilogue(const Problem &p, int row0, int G,
                 if (c0 + 4 < nb) process(c0 + 4, nB, mB);
             }
         }
+        FD_PHASE(6);
         uint2 o;
         o.x = (unsigned)to_half_bits(s[0] / l) | ((unsigned)to_half_bits(s[1] / l) << 16);
         o.y = (unsigned)to_half_bits(s[2] / l) | ((unsigned)to_half_bits(s[3] / l) << 16);

@@ -65,8 +65,10 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     const int c = ELECT ? j / groups8 : j % p.nc;
     const int row = (blockIdx.x & 7) + 8 * (ELECT ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
+    FD_PHASE(0);
     int S;
     const bool flagged = chunk_body<C, NW, UP, false, C, EARLY, PAGED>(p, row, c, lds, &S);
+    FD_PHASE(3);
     const int nb = (S + p.C - 1) / p.C;        // chunks of this row that hold a valid key
     if (c >= nb) {                             // padding chunk: zero partials were written
         if (nb == 0 && c == 0 && ELECT) {    // empty sequence: nobody else owns the row
@@ -85,12 +87,18 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     // last arrival owns the row and reads the others' results past the caches.
     wait_stores_performed();
     __syncthreads();
+    FD_PHASE(4);
     if (tid == 0) lds.last = arrive_and_elect(p, row, c, nb);
     __syncthreads();
+    FD_PHASE(5);
     if (!lds.last) return;
     // up to 8 chunks: 32 threads walk them in registers (one round trip, no LDS, no barrier)
     if (nb <= 8) group_epilogue(p, row, 1, nb);
     else row_epilogue<NW, true>(p, row, nb, [nb] { return nb; }, &lds.acc[0][0]);
+#ifdef FD_PHASE_PROBE
+    wait_stores_performed();
+    FD_PHASE(7);
+#endif
 }
 
 // First launch of the literal chain: Eq. 4 inner sums and the range guard, nothing else (no
@@ -243,6 +251,18 @@ template <int C> struct SyncLauncher {
 };
 
 }  // namespace
+
+#ifdef FD_PHASE_PROBE
+// Probe build only: copies the phase log of the last fused per-row launch to the host
+// (synchronizes the device).  `n` = number of 64-bit stamps wanted, <= 4096 * 8.
+extern "C" int fd_phase_probe_read(unsigned long long *host_dst, size_t n)
+{
+    if (!host_dst || n > (size_t)kPhaseMaxGrid * kPhaseSlots) return 1;
+    if (hipDeviceSynchronize() != hipSuccess) return 6;
+    return hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(fd_phase_log), n * sizeof(unsigned long long), 0,
+                               hipMemcpyDeviceToHost) == hipSuccess ? 0 : 6;
+}
+#endif
 
 hipError_t launch_decode_fused(const Problem &p, hipStream_t s)
 {

@@ -48,57 +48,65 @@ class FdError(RuntimeError):
 
 _vp, _f = ctypes.c_void_p, ctypes.c_float
 _sp = ctypes.POINTER(Shape)
-_lib.fd_workspace_bytes.restype = ctypes.c_size_t
-_lib.fd_workspace_bytes.argtypes = [_sp]
-_lib.fd_pick_chunk.restype = ctypes.c_int32
-_lib.fd_pick_chunk.argtypes = [_sp]
-_lib.fd_status_str.restype = ctypes.c_char_p
-_lib.fd_status_str.argtypes = [ctypes.c_int]
-for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel"):
-    getattr(_lib, _name).restype = ctypes.c_int
-    getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
-_lib.fd_decode_attn_static.restype = ctypes.c_int
-_lib.fd_decode_attn_static.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, _vp]
-_lib.fd_decode_attn_sync.restype = ctypes.c_int
-_lib.fd_decode_attn_sync.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, Workspace, _vp]
-for _name in ("fd_decode_attn_partial", "fd_decode_attn_gqa_partial"):
-    getattr(_lib, _name).restype = ctypes.c_int
-    getattr(_lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, Workspace, _vp]
-_lib.fd_get_flags.restype = ctypes.c_int
-_lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
-_lib.fd_get_partials.restype = ctypes.c_int
-_lib.fd_get_partials.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 2
 
-_lib.fd_workspace_init.restype = ctypes.c_int
-_lib.fd_workspace_init.argtypes = [_sp, Workspace, _vp]
-_lib.fd_list_flagged_rows.restype = ctypes.c_int
-_lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
 
 class Calibration(ctypes.Structure):
     _fields_ = [("apply", ctypes.c_int32), ("phi", ctypes.c_float), ("bounds", Bounds),
                 ("x_lo", ctypes.c_float), ("x_hi", ctypes.c_float), ("covered", ctypes.c_double)]
 
 
-_lib.fd_logit_histogram.restype = ctypes.c_int
-_lib.fd_logit_histogram.argtypes = [_sp, _vp, _vp, _vp, _f, _f, ctypes.c_int32, _vp, _vp, _vp]
-_lib.fd_calibrate.restype = ctypes.c_int
-_lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _f, _f, ctypes.c_double, _f, _f,
-                              ctypes.c_int32, ctypes.POINTER(Calibration)]
+def _bind(lib):
+    """Declare the argument and result types of every entry point on a loaded library."""
+    lib.fd_workspace_bytes.restype = ctypes.c_size_t
+    lib.fd_workspace_bytes.argtypes = [_sp]
+    lib.fd_pick_chunk.restype = ctypes.c_int32
+    lib.fd_pick_chunk.argtypes = [_sp]
+    lib.fd_status_str.restype = ctypes.c_char_p
+    lib.fd_status_str.argtypes = [ctypes.c_int]
+    for _name in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_multikernel"):
+        getattr(lib, _name).restype = ctypes.c_int
+        getattr(lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+    lib.fd_decode_attn_static.restype = ctypes.c_int
+    lib.fd_decode_attn_static.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, _vp]
+    lib.fd_decode_attn_sync.restype = ctypes.c_int
+    lib.fd_decode_attn_sync.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, Workspace, _vp]
+    for _name in ("fd_decode_attn_partial", "fd_decode_attn_gqa_partial"):
+        getattr(lib, _name).restype = ctypes.c_int
+        getattr(lib, _name).argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, Workspace, _vp]
+    lib.fd_get_flags.restype = ctypes.c_int
+    lib.fd_get_flags.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 4
+    lib.fd_get_partials.restype = ctypes.c_int
+    lib.fd_get_partials.argtypes = [_sp, Workspace] + [ctypes.POINTER(_vp)] * 2
 
-_lib.fd_decode_attn_paged.restype = ctypes.c_int
-_lib.fd_decode_attn_paged.argtypes = [_sp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp, Workspace, _vp]
-_lib.fd_decode_attn_paged_append.restype = ctypes.c_int
-_lib.fd_decode_attn_paged_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp,
-                                            Workspace, _vp]
-_lib.fd_decode_attn_append.restype = ctypes.c_int
-_lib.fd_decode_attn_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+    lib.fd_workspace_init.restype = ctypes.c_int
+    lib.fd_workspace_init.argtypes = [_sp, Workspace, _vp]
+    lib.fd_list_flagged_rows.restype = ctypes.c_int
+    lib.fd_list_flagged_rows.argtypes = [_sp, _vp, Workspace, _vp]
 
-_lib.fd_prefill_workspace_bytes.restype = ctypes.c_size_t
-_lib.fd_prefill_workspace_bytes.argtypes = [_sp]
-_lib.fd_prefill_attn.restype = ctypes.c_int
-_lib.fd_prefill_attn.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
-_lib.fd_prefill_get_flags.restype = ctypes.c_int
-_lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
+    lib.fd_logit_histogram.restype = ctypes.c_int
+    lib.fd_logit_histogram.argtypes = [_sp, _vp, _vp, _vp, _f, _f, ctypes.c_int32, _vp, _vp, _vp]
+    lib.fd_calibrate.restype = ctypes.c_int
+    lib.fd_calibrate.argtypes = [ctypes.POINTER(ctypes.c_uint64), ctypes.c_int32, _f, _f, ctypes.c_double, _f, _f,
+                                  ctypes.c_int32, ctypes.POINTER(Calibration)]
+
+    lib.fd_decode_attn_paged.restype = ctypes.c_int
+    lib.fd_decode_attn_paged.argtypes = [_sp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp, Workspace, _vp]
+    lib.fd_decode_attn_paged_append.restype = ctypes.c_int
+    lib.fd_decode_attn_paged_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int32, ctypes.c_int32, _vp, _f, Bounds, _vp,
+                                                Workspace, _vp]
+    lib.fd_decode_attn_append.restype = ctypes.c_int
+    lib.fd_decode_attn_append.argtypes = [_sp, _vp, _vp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+
+    lib.fd_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.fd_prefill_workspace_bytes.argtypes = [_sp]
+    lib.fd_prefill_attn.restype = ctypes.c_int
+    lib.fd_prefill_attn.argtypes = [_sp, _vp, _vp, _vp, _vp, _f, Bounds, _vp, Workspace, _vp]
+    lib.fd_prefill_get_flags.restype = ctypes.c_int
+    lib.fd_prefill_get_flags.argtypes = [_sp, Workspace, ctypes.POINTER(_vp)]
+    return lib
+
+
+_lib = _bind(_lib)
 
 EXPORTS = ("fd_decode_attn_static", "fd_decode_attn_paged", "fd_decode_attn_paged_append", "fd_prefill_workspace_bytes", "fd_prefill_attn", "fd_prefill_get_flags", "fd_decode_attn_append", "fd_logit_histogram", "fd_calibrate", "fd_workspace_bytes", "fd_pick_chunk", "fd_workspace_init", "fd_decode_attn", "fd_decode_attn_gqa",
            "fd_decode_attn_multikernel", "fd_decode_attn_sync", "fd_list_flagged_rows",

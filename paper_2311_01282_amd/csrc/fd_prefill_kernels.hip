@@ -13,7 +13,8 @@
 //            the B operand of the second product, no data movement.
 //   weights  P = e^{s S^T - phi}, fp32, guard, causal mask.  fp16 cannot hold e^{x - phi}
 //            over the admissible range and bf16 has 8 significant bits, so P goes to the
-//            matrix cores as bf16 hi + lo (16 bits).
+//            matrix cores as bf16 hi + lo (16 bits) -- as hi + mid + lo (24 bits) in the
+//            first query tile, whose queries see few keys.
 //   output   O^T[d][query] = V^T . P^T       A = V^T from a transposed copy of V that a
 //            small pass writes first (keys contiguous per d, so the loop transposes
 //            nothing), likewise split into bf16 hi + lo whose sum is the fp16 value
@@ -147,7 +148,12 @@ __device__ __forceinline__ int k_slot(int r, int c)
     return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 3) << 2))) << 4);
 }
 
-template <bool ONLINE>
+// P3: the weights go to the matrix cores as THREE bf16 pieces (all 24 bits of the fp32 value; five
+// products per tile) instead of two (16 bits; three products).  Used for the first query tile
+// only: two pieces leave up to 2^-18 * |v| on an output element, which shows against the
+// relative tolerance only where a query sees so few keys that its terms can cancel to near zero
+// without the rounding errors averaging out -- the queries of the first tile.
+template <bool ONLINE, bool P3>
 __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -212,7 +218,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     // the loads of this wavefront have landed in LDS
     auto fetched = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
     // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
-    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2], bf16x8 &pB, bf16x8 &pBl, int k0) {
+    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2], bf16x8 &pB, bf16x8 &pBl, bf16x8 &pBm, int k0) {
         constexpr bool MASKED = decltype(masked)::value;
         const int qrow = w0 + 16 * qb + n;
         float z[8];
@@ -268,17 +274,32 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             }
             shift = mnew == -INFINITY ? 0.f : mnew;
         }
-        unsigned hi[4], lo[4];
+        unsigned hi[4], lo[4], mid[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             f32x2 e = {__builtin_amdgcn_exp2f(z[2 * j] - shift), __builtin_amdgcn_exp2f(z[2 * j + 1] - shift)};
             den[qb] += e[0] + e[1];
-            hi[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
-            const f32x2 top = {__builtin_bit_cast(float, hi[j] << 16), __builtin_bit_cast(float, hi[j] & 0xffff0000u)};
-            lo[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e - top, bf16x2));        // e - top is exact
+            if constexpr (P3) {
+                // three pieces by truncation: hi = the upper 16 bits of e, mid = the upper 16 bits of
+                // what that leaves (exact in fp32), lo = the rest (at most 8 significant bits: exact)
+                // (the elements are taken by value first: bit-casting a vector element in place is unreliable)
+                const float e0 = e[0], e1 = e[1];
+                const unsigned t0 = __builtin_bit_cast(unsigned, e0), t1 = __builtin_bit_cast(unsigned, e1);
+                const float r0 = e0 - __builtin_bit_cast(float, t0 & 0xffff0000u), r1 = e1 - __builtin_bit_cast(float, t1 & 0xffff0000u);
+                const unsigned u0 = __builtin_bit_cast(unsigned, r0), u1 = __builtin_bit_cast(unsigned, r1);
+                const float w0 = r0 - __builtin_bit_cast(float, u0 & 0xffff0000u), w1 = r1 - __builtin_bit_cast(float, u1 & 0xffff0000u);
+                hi[j] = (t0 >> 16) | (t1 & 0xffff0000u);
+                mid[j] = (u0 >> 16) | (u1 & 0xffff0000u);
+                lo[j] = (__builtin_bit_cast(unsigned, w0) >> 16) | (__builtin_bit_cast(unsigned, w1) & 0xffff0000u);
+            } else {
+                hi[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
+                const f32x2 top = {__builtin_bit_cast(float, hi[j] << 16), __builtin_bit_cast(float, hi[j] & 0xffff0000u)};
+                lo[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e - top, bf16x2));        // e - top is exact
+            }
         }
         pB = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
         pBl = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
+        pBm = __builtin_bit_cast(bf16x8, u32x4{mid[0], mid[1], mid[2], mid[3]});
     };
     // one step of this wavefront on the tiles in LDS buffer `buf`
     auto compute = [&](auto masked, int s, int buf) {
@@ -316,8 +337,8 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         };
 #pragma unroll
         for (int dt = 0; dt < kVAhead; ++dt) read_v(dt, dt);
-        bf16x8 pB[kQB], pBl[kQB];
-        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], k0);
+        bf16x8 pB[kQB], pBl[kQB], pBm[kQB];
+        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], pBm[qb], k0);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
             if (dt + kVAhead < 8) read_v(dt + kVAhead, (dt + kVAhead) % (kVAhead + 1));
@@ -328,9 +349,16 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pB[qb], acc[dt][qb], 0, 0, 0);
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBl[qb], acc[dt][qb], 0, 0, 0);
-            // keep the order: the next tile's two LDS reads, then this tile's six MFMAs
+            if constexpr (P3) {
+                // P = hi + mid + lo: + Vh Pm + Vl Pm (Vl Pl and below are under 2^-24 of a term)
+#pragma unroll
+                for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBm[qb], acc[dt][qb], 0, 0, 0);
+#pragma unroll
+                for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pBm[qb], acc[dt][qb], 0, 0, 0);
+            }
+            // keep the order: the next tile's two LDS reads, then this tile's MFMAs
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 3 * kQB, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, (P3 ? 5 : 3) * kQB, 0);
         }
     };
 
@@ -426,10 +454,12 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillProblem p)
             p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + i0 / 64 + threadIdx.x] = 0;
         return;
     }
-    const bool flagged = tile_all<false>(p, lds, b, hq, i0, S);
+    // the first query tile (queries that see 128 keys or fewer) carries its weights with all 24 bits
+    const bool flagged = i0 == 0 ? tile_all<false, true>(p, lds, b, hq, i0, S) : tile_all<false, false>(p, lds, b, hq, i0, S);
     if (flagged) {                                       // Section 3 "Recomputation", for this tile
         __syncthreads();
-        tile_all<true>(p, lds, b, hq, i0, S);
+        if (i0 == 0) tile_all<true, true>(p, lds, b, hq, i0, S);
+        else tile_all<true, false>(p, lds, b, hq, i0, S);
     }
 }
 

@@ -20,16 +20,9 @@ def H():
     return fd_harness
 
 
-# The prompt-phase kernel feeds its weights to the matrix cores as bf16 hi + lo, both rounded to
-# nearest: 2^-18 of a term.  In a row of a handful of keys whose terms nearly cancel, that is up
-# to 2^-18 * max|v| = 1.7e-5 on an element near zero (a randomized sweep of short prompts found
-# 1.05e-5 on 8.8e-4), so the relative error is measured against max(|oracle|, 2e-3) here, where the
-# decode tests use 1e-3; the absolute bound (2e-3) and the relative one (1e-2) are the same.
-PREFILL_REL_FLOOR = 2e-3
-
-
 def close(H, got, want, what):
-    return H.assert_close(got, want, what, rel_floor=PREFILL_REL_FLOOR)
+    """The decode tolerance: 2e-3 absolute, 1e-2 relative against max(|oracle|, 1e-3)."""
+    return H.assert_close(got, want, what)
 
 
 def draw(B, Hq, Hkv, Smax, lens, seed, poison=True):
@@ -222,13 +215,14 @@ def test_prefill_rejects_bad_arguments():
 
 
 def test_short_prompts_sweep(H):
-    """Rows of a handful of keys are where the bf16 hi + lo weights show (see PREFILL_REL_FLOOR):
-    forty seeded short prompts, every row against the oracle."""
+    """Rows of a handful of keys are where the bf16 hi + lo weights show (the first query tile carries them with all 24 bits for that reason):
+    200 seeded short prompts (lengths 1 .. 320, so that queries just past the first tile are covered too), every row
+    against the oracle at the decode tolerance."""
     scale = float(np.float32(1.0 / np.sqrt(128.0)))
-    for seed in range(100, 140):
+    for seed in range(100, 300):
         rng = np.random.default_rng(seed)
         B = int(rng.integers(1, 4)); Hkv = int(rng.choice([1, 2, 4])); Hq = Hkv * int(rng.choice([1, 2, 4]))
-        Smax = int(rng.integers(16, 200))
+        Smax = int(rng.integers(16, 200 if seed < 250 else 321))
         lens = [int(x) for x in rng.integers(1, Smax + 1, size=B)]
         q, k, v, sl = draw(B, Hq, Hkv, Smax, lens, seed=90000 + seed)
         rows = pf.all_rows(B, Hq, Smax)

@@ -103,6 +103,10 @@ fd::WsView view(const Layout &L, fd_workspace ws)
 
 inline bool misaligned(const void *p) { return ((uintptr_t)p % 16) != 0; }
 
+#ifdef FD_PHASE_PROBE
+int g_probe_scatter = 0;       // probe build only: see Problem::scatter
+#endif
+
 fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const void *v,
                        const int32_t *seq_lens, void *out, bool need_out, fd_workspace ws,
                        fd::Problem *p)
@@ -132,6 +136,9 @@ fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const v
     p->k_store = p->v_store = nullptr;
     p->block_table = nullptr;
     p->pages_per_seq = 0; p->page_shift = 0; p->n_pages = 0;
+#ifdef FD_PHASE_PROBE
+    p->scatter = g_probe_scatter;
+#endif
     return FD_OK;
 }
 
@@ -745,6 +752,12 @@ fd_status fd_prefill_get_flags(const fd_shape *shape, fd_workspace ws, const uin
     if (tile_flags) *tile_flags = reinterpret_cast<const uint8_t *>(static_cast<char *>(ws.ptr) + P.flags);
     return FD_OK;
 }
+
+#ifdef FD_PHASE_PROBE
+// Probe build only (not in the product library, not in the header): deal the chunks of a row to
+// different XCDs from the next call on.
+void fd_phase_probe_scatter(int on) { g_probe_scatter = on ? 1 : 0; }
+#endif
 
 const char *fd_status_str(fd_status status)
 {

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     const int groups8 = (groups + 7) >> 3;
     const int j = blockIdx.x >> 3;
     const int c = p.chunk_major ? j / groups8 : j % p.nc;
-    const int gi = (blockIdx.x & 7) + 8 * (p.chunk_major ? j - c * groups8 : j / p.nc);
+    const int gi = row_slot(p, blockIdx.x & 7, c) + 8 * (p.chunk_major ? j - c * groups8 : j / p.nc);
     if (gi >= groups) return;
     const int b = gi / p.Hkv;
     const int row0 = b * p.Hq + (gi - b * p.Hkv) * G;       // first query row of the group

@@ -64,7 +64,23 @@ struct Problem {
     // page = 1 << page_shift.  Smax is the logical capacity pages_per_seq * page.
     const int32_t *block_table;
     int pages_per_seq, page_shift, n_pages;
+#ifdef FD_PHASE_PROBE
+    // Probe build only: 1 = deal the chunks of a row (head group) to DIFFERENT XCDs -- chunk c of row r
+    // to XCD (r + c) % 8 -- instead of all to XCD r % 8, so that every hand-over of the fused kernels
+    // crosses from one XCD's L2 to another's (tests of the hand-over's coherence; timing of its cost).
+    int scatter;
+#endif
 };
+
+// XCD slot (workgroup index modulo 8) -> the row, or head group, within its block of 8 that the
+// workgroup serves: the slot itself, or -- probe build, scatter on -- the slot rotated by the chunk.
+__device__ __forceinline__ int row_slot(const Problem &p, int slot, int c)
+{
+#ifdef FD_PHASE_PROBE
+    if (p.scatter) return (slot - c) & 7;
+#endif
+    return slot;
+}
 
 // Number of keys resident in the cache: the clamped entry of seq_lens.
 __device__ __forceinline__ int clamp_len(const Problem &p, int raw)

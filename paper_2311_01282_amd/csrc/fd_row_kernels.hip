@@ -63,7 +63,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
     const int c = ELECT ? j / groups8 : j % p.nc;
-    const int row = (blockIdx.x & 7) + 8 * (ELECT ? j - c * groups8 : j / p.nc);
+    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (ELECT ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     FD_PHASE(0);
     int S;

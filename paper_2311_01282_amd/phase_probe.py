@@ -35,6 +35,7 @@ def main():
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--rounds", type=int, default=12)
     ap.add_argument("--calls", type=int, default=40)
+    ap.add_argument("--scatter", action="store_true", help="deal the chunks of a row to eight different XCDs (every hand-over then crosses L2s)")
     ap.add_argument("--detail", action="store_true", help="also: when the workgroups finish their chunk loop, by XCD and by chunk index")
     args = ap.parse_args()
 
@@ -48,6 +49,9 @@ def main():
     lib = fdattn._bind(ctypes.CDLL(path))
     lib.fd_phase_probe_read.restype = ctypes.c_int
     lib.fd_phase_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t]
+    lib.fd_phase_probe_scatter.restype = None
+    lib.fd_phase_probe_scatter.argtypes = [ctypes.c_int]
+    lib.fd_phase_probe_scatter(1 if args.scatter else 0)
 
     cfg = synth.CONFIGS[args.workload]
     B, Hq, Hkv, D, Smax = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["D"], cfg["Smax"]
@@ -119,8 +123,8 @@ def main():
                             np.array([np.median(rel[(wg >> 3) // groups8 == c, 3]) for c in range(nc)]),
                             np.array([np.median(rel[(wg & 7) == x, 1]) for x in range(8)])))
     med = lambda xs: statistics.median(xs)
-    print("workload %s, chunk %d, %d workgroups, %d rounds of %d back-to-back calls (last call of each round)"
-          % (args.workload, chunk, grid, args.rounds, args.calls))
+    print("workload %s, chunk %d, %d workgroups, %d rounds of %d back-to-back calls (last call of each round)%s"
+          % (args.workload, chunk, grid, args.rounds, args.calls, "; chunks of a row on 8 different XCDs" if args.scatter else ""))
     print("event-timed call in the same loops: %.2f us (median of rounds)" % med(ev_us))
     print()
     print("| phase (thread 0 of each workgroup) | earliest wg, us | median wg, us | latest wg, us | median step from previous phase, us |")

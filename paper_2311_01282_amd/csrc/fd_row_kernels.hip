@@ -137,42 +137,60 @@ template <int C> struct ChainTune {
 template <int C>
 __global__ __launch_bounds__(ChainTune<C>::NW * 64) void chain_combine_kernel(const Problem p)
 {
-    constexpr int NW = ChainTune<C>::NW, UP = ChainTune<C>::UP, NT = NW * 64;
+    constexpr int NW = ChainTune<C>::NW, UP = ChainTune<C>::UP;
+    constexpr int KB = NW * 2;                  // items per batch: one per half wavefront
     __shared__ ChunkLds<NW, C> lds;
-    const int tid = threadIdx.x;
+    __shared__ int item_flag[KB];
+    const int tid = threadIdx.x, half = tid >> 5, j = tid & 31;
     const long long items = (long long)p.rows * p.nc;
-    for (long long w = blockIdx.x; w < items; w += gridDim.x) {
-        const int row = (int)(w / p.nc), c = (int)(w % p.nc);
-        const int S = valid_len(p, row / p.Hq);
-        const int nb = (S + p.C - 1) / p.C;
-        const uint8_t *cf = p.ws.chunk_flags + (size_t)row * p.nc;
+    // Workgroups stride over the items (the chunks of a flagged row go to different workgroups) and
+    // take them in batches of KB: the row flags of a whole batch are fetched at once -- 32 threads
+    // per item OR the row's chunk flags -- so a batch of clean rows costs one memory round trip.
+    // All nc slots are read: chunks without a valid key carry flag 0 and zero sums, so neither the
+    // decision nor the outer sums need the sequence length.
+    for (long long w0 = blockIdx.x; w0 < items; w0 += (long long)KB * gridDim.x) {
+        const long long mine = w0 + (long long)half * gridDim.x;
         int f = 0;
-        for (int i = tid; i < nb; i += NT) f |= cf[i];
-        const int flagged = __syncthreads_or(f);
-        if (c == 0 && tid == 0) p.ws.row_flags[row] = flagged ? 1 : 0;
-        if (flagged) {
-            if (c < nb) chunk_body<C, NW, UP, true>(p, row, c, lds);
-        } else if (c == 0) {
-            // 4 slices of 128 threads; slice k adds chunks k, k+4, ...; the slices are added in order
-            const int slice = tid >> 7, t = tid & 127;
-            const float *num = p.ws.num + (size_t)row * p.nc * kHeadDim + t;
-            const float *den = p.ws.den + (size_t)row * p.nc;
-            float s = 0.f, l = 0.f;
+        if (mine < items) {
+            const uint8_t *cf = p.ws.chunk_flags + (size_t)(mine / p.nc) * p.nc;
+            for (int i = j; i < p.nc; i += 32) f |= cf[i];
+        }
+        const unsigned long long any = __ballot(f != 0);
+        if (j == 0) item_flag[half] = ((any >> (32 * (half & 1))) & 0xffffffffull) != 0ull;
+        __syncthreads();
+        for (int k = 0; k < KB; ++k) {
+            const long long w = w0 + (long long)k * gridDim.x;
+            if (w >= items) break;
+            const int row = (int)(w / p.nc), c = (int)(w % p.nc);
+            const int flagged = item_flag[k];
+            if (c == 0 && tid == 0) p.ws.row_flags[row] = flagged ? 1 : 0;
+            if (flagged) {
+                chunk_body<C, NW, UP, true>(p, row, c, lds);                // (a chunk without keys leaves at once)
+                __syncthreads();                                             // lds is reused by the next item
+            } else if (c == 0) {
+                // 4 slices of 128 threads; slice s adds chunks s, s+4, ...; the slices are added in order
+                const int slice = tid >> 7, t = tid & 127;
+                const float *num = p.ws.num + (size_t)row * p.nc * kHeadDim + t;
+                const float *den = p.ws.den + (size_t)row * p.nc;
+                float s = 0.f, l = 0.f;
 #pragma unroll 4
-            for (int i = slice; i < nb; i += 4) {
-                s += num[(size_t)i * kHeadDim];
-                l += den[i];
-            }
-            lds.acc[slice][t] = s;
-            if (t == 0) lds.den[slice] = l;
-            __syncthreads();
-            if (tid < kHeadDim) {
-                const float st = ((lds.acc[0][t] + lds.acc[1][t]) + lds.acc[2][t]) + lds.acc[3][t];
-                const float lt = ((lds.den[0] + lds.den[1]) + lds.den[2]) + lds.den[3];
-                p.out[(size_t)row * kHeadDim + t] = nb > 0 ? to_half_bits(st / lt) : (uint16_t)0;
+                for (int i = slice; i < p.nc; i += 4) {
+                    s += num[(size_t)i * kHeadDim];
+                    l += den[i];
+                }
+                lds.acc[slice][t] = s;
+                if (t == 0) lds.den[slice] = l;
+                __syncthreads();
+                if (tid < kHeadDim) {
+                    const float st = ((lds.acc[0][t] + lds.acc[1][t]) + lds.acc[2][t]) + lds.acc[3][t];
+                    const float lt = ((lds.den[0] + lds.den[1]) + lds.den[2]) + lds.den[3];
+                    // an empty sequence has no term at all: zeros
+                    p.out[(size_t)row * kHeadDim + t] = lt > 0.f ? to_half_bits(st / lt) : (uint16_t)0;
+                }
+                __syncthreads();
             }
         }
-        __syncthreads();                        // lds is reused by the next item
+        __syncthreads();                        // item_flag is rewritten by the next batch
     }
 }
 
@@ -235,8 +253,8 @@ template <int C> struct ChainCombineLauncher {
     {
         const long long items = (long long)p.rows * p.nc;
         if (items == 0) return hipSuccess;
-        // two workgroups of 8 wavefronts fit a compute unit: a few rounds' worth, striding over the items
-        const unsigned grid = (unsigned)(items < 2048 ? items : 2048);
+        // two workgroups of 8 wavefronts fit a compute unit: one round of the chip, striding over the items
+        const unsigned grid = (unsigned)(items < 512 ? items : 512);
         return launch(chain_combine_kernel<C>, dim3(grid), dim3(ChainTune<C>::NW * 64), s, p);
     }
 };

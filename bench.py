@@ -307,7 +307,8 @@ def prefill(args):
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / sec / 1e12, 1),
                      "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(flops / sec / 1e12 / MFMA_PEAK_TFLOPS, 4),
                      "algorithmic_flops_per_launch": flops,
-                     "note": "whole call (transpose pass + attention); useful flops 4*D per causal (query, key) pair",
+                     "note": "whole call (transpose pass + attention); useful flops 4*D per causal (query, key) pair; the second "
+                             "product runs twice (fp16 hi + lo weights): the kernel issues 1.5x the useful flops",
                      "traffic": None},
         "cpu_baseline": {"value": round(4.0 * D * m["cpu_pairs"] / m["t_cpu"] / 1e12, 6), "unit": "TFLOP/s", "cores": m["ncpu"],
                          "kind": "oracle", "sample": "%d sampled query rows of the same prompt (%d query-key pairs), fp64"

@@ -429,16 +429,18 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
  *            i >= n_b of out are set to zero, keys >= n_b are never used.
  * shape->chunk is ignored.  `ws`: device scratch of fd_prefill_workspace_bytes(shape)
  * bytes, 256-byte aligned, arbitrary previous contents (it receives a transposed
- * bf16 hi/lo copy of V and one flag byte per (row head, 64-query tile)); no
- * initialisation call is needed.  Arithmetic: fp16 products with fp32 accumulation
- * for the scores; fp32 exponentials, which enter the second product as bf16 hi + lo
- * pairs (16 significant bits) -- as three bf16 pieces (all 24 bits) for the first 128
- * queries of a prompt, the ones that see so few keys that a 16-bit weight could show in
- * an output element that cancels to near zero; the denominator sums the fp32 values; V
- * exact as bf16 hi + lo.  Guard: as in decode a logit outside the bounds flags, and so
- * does a NaN logit; the comparison is made on log2 e^{x - phi} = fma(<q,k>, scale * log2 e,
- * -phi * log2 e) against the bounds times log2 e, so a logit within fp32 rounding of a
- * bound may fall on either side of it (decode compares x * scale - phi itself).
+ * copy of V and one flag byte per (row head, 64-query tile)); no initialisation call
+ * is needed.  Arithmetic: fp16 products with fp32 accumulation for the scores; fp32
+ * exponentials and denominators; the weights enter the second product as fp16 hi + lo
+ * pairs (22 significant bits) under a scale 2^k of the query's own, fixed after the
+ * query's first 32 keys (it cancels in the division and is constant over the keys, so
+ * partial sums still just add); V is used as it is.  A query whose later weights exceed
+ * that scale's headroom (a logit more than 8.2 above the largest of its first 32) has
+ * its 128-query tile redone with the synchronized scheme: same result, NO flag (the
+ * flags report the guard alone).  Guard: as in decode a logit outside the bounds flags,
+ * and so does a NaN logit; the comparison is made on log2 e^{x - phi} (plus k) against
+ * the bounds times log2 e (plus k), so a logit within fp32 rounding of a bound may fall
+ * on either side of it (decode compares x * scale - phi itself).
  * Errors as for fd_decode_attn; FD_ERR_UNSUPPORTED beyond 65535 heads, sequences
  * or batch * n_kv_heads.
  */

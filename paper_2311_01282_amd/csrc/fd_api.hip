@@ -684,7 +684,7 @@ fd_status fd_calibrate(const uint64_t *hist, int32_t n_bins, float x_min, float 
 }
 
 namespace {
-struct PrefillLayout { size_t vt_hi, vt_lo, flags, total; int spad, tiles; };
+struct PrefillLayout { size_t vt, flags, total; int spad, tiles; };
 fd_status plan_prefill(const fd_shape *shape, PrefillLayout *P)
 {
     if (!shape) return FD_ERR_NULL;
@@ -697,8 +697,7 @@ fd_status plan_prefill(const fd_shape *shape, PrefillLayout *P)
     P->tiles = P->spad / 64;
     const size_t vt = (size_t)sh.batch * sh.n_kv_heads * fd::kHeadDim * P->spad * sizeof(uint16_t);
     size_t off = 0;
-    P->vt_hi = off;  off = align_up(off + vt);
-    P->vt_lo = off;  off = align_up(off + vt);
+    P->vt = off;     off = align_up(off + vt);
     P->flags = off;  off = align_up(off + (size_t)sh.batch * sh.n_q_heads * P->tiles);
     P->total = off;
     return FD_OK;
@@ -733,8 +732,7 @@ fd_status fd_prefill_attn(const fd_shape *shape, const void *q, const void *k_ca
     p.v = static_cast<const uint16_t *>(v_cache);
     p.seq_lens = seq_lens;
     p.out = static_cast<uint16_t *>(out);
-    p.vt_hi = reinterpret_cast<uint16_t *>(base + P.vt_hi);
-    p.vt_lo = reinterpret_cast<uint16_t *>(base + P.vt_lo);
+    p.vt = reinterpret_cast<uint16_t *>(base + P.vt);
     p.tile_flags = reinterpret_cast<uint8_t *>(base + P.flags);
     p.B = shape->batch; p.Hq = shape->n_q_heads; p.Hkv = shape->n_kv_heads; p.G = p.Hq / p.Hkv;
     p.Smax = shape->max_seq; p.Spad = P.spad; p.tiles = P.tiles;

@@ -129,7 +129,7 @@ struct PrefillProblem {
     const uint16_t *q, *k, *v;   // q [B, Hq, Smax, D]; k, v [B, Hkv, Smax, D]
     const int32_t *seq_lens;
     uint16_t *out;               // [B, Hq, Smax, D]
-    uint16_t *vt_hi, *vt_lo;     // workspace: V transposed per KV head, tiled [Spad / 32][4][D][8 keys], bf16 bit patterns, hi + lo = V
+    uint16_t *vt;                // workspace: V transposed per KV head, tiled [Spad / 32][4][D][8 keys], fp16
     uint8_t *tile_flags;         // workspace: [B, Hq, tiles]
     int B, Hq, Hkv, G, Smax, Spad, tiles;   // Spad = Smax rounded up to 64; tiles = Spad / 64
     float scale, phi, lo, hi;

@@ -11,15 +11,19 @@
 //            k0 + 8g + 4t + r: with that permutation the two score tiles of a 32-key
 //            step leave lane (n, g) holding keys k0 + 8g .. 8g + 7 of query n -- exactly
 //            the B operand of the second product, no data movement.
-//   weights  P = e^{s S^T - phi}, fp32, guard, causal mask.  fp16 cannot hold e^{x - phi}
-//            over the admissible range and bf16 has 8 significant bits, so P goes to the
-//            matrix cores as bf16 hi + lo (16 bits) -- as hi + mid + lo (24 bits) in the
-//            first query tile, whose queries see few keys.
+//   weights  P = e^{s S^T - phi}, fp32, guard, causal mask.  They go to the matrix cores as fp16
+//            hi + lo pairs (22 significant bits).  fp16 has the precision but not the range of
+//            e^{x - phi} over the admissible x - phi, so every query carries a scale of its own,
+//            2^{k_q}, fixed after its first key step so that the largest weight seen there becomes
+//            2^4: numerator and denominator of a query are both scaled by it and it cancels in the
+//            division; being constant over the keys of a query it leaves the sums of Eq. 4 as
+//            they are -- partial sums still just add, nothing is ever rescaled.  A query whose later
+//            logits exceed its first step's maximum by more than 2^11.9 would overflow fp16: its
+//            tile is redone with the synchronized scheme, like a tile whose guard fired (but
+//            without raising the guard's flag).
 //   output   O^T[d][query] = V^T . P^T       A = V^T from a transposed copy of V that a
 //            small pass writes first (keys contiguous per d, so the loop transposes
-//            nothing), likewise split into bf16 hi + lo whose sum is the fp16 value
-//            exactly.  Three MFMAs per tile (Vh Ph + Vl Ph + Vh Pl) buy fp16-grade results
-//            from bf16 matrix cores.
+//            nothing); V is fp16 as it is.  Two MFMAs per tile (V Ph + V Pl).
 // K and V^T tiles are loaded from global memory straight into LDS, once per workgroup, and
 // shared by its four wavefronts (double-buffered; layouts free of bank conflicts for the
 // 16-byte operand reads).
@@ -30,25 +34,17 @@ namespace fd {
 namespace {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr float kFirstStepLog2 = 4.f;     // a query's largest weight of its first key step becomes 2^4 ...
+constexpr float kOverflowLog2 = 15.9f;    // ... and no later weight may reach 2^16 (fp16 ends at 65504)
 
 constexpr int kQB = 2;            // 16-query blocks per wavefront (1: 401, 2: 471-500 TFLOP/s at 8K)
 constexpr int kWaveQ = 16 * kQB;  // queries per wavefront
 constexpr int kQTile = 4 * kWaveQ; // query rows per workgroup
 constexpr int kStep = 32;        // keys per wavefront step
 constexpr int kVAhead = 1;    // V^T operand tiles read from LDS ahead of the MFMAs that use them
-
-// fp32 -> bf16 bit pattern, round to nearest even (finite inputs; NaN stays NaN).
-__device__ __forceinline__ unsigned bf16_bits(float x)
-{
-    const unsigned u = __builtin_bit_cast(unsigned, x);
-    if (x != x) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ float bf16_value(unsigned bits) { return __builtin_bit_cast(float, bits << 16); }
 
 // V^T of one KV head is stored tile by tile, in the order the attention kernel consumes it:
 // [32-key step][8-key chunk g][d][8 keys], so the 8 KiB a step needs are contiguous (whole
@@ -59,10 +55,10 @@ __device__ __forceinline__ size_t vt_offset(int key, int d)
     return (size_t)(key >> 5) * (32 * kHeadDim) + (size_t)((((key >> 3) & 3) * kHeadDim + d) << 3);
 }
 
-// ---- pass 0: V [B,Hkv,Smax,D] fp16 -> tiled V^T hi/lo (Spad keys) bf16, zero beyond the prompt ----
+// ---- pass 0: V [B,Hkv,Smax,D] fp16 -> tiled V^T (Spad keys) fp16, zero beyond the prompt ----
 __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p)
 {
-    __shared__ float tile[64][kHeadDim + 1];
+    __shared__ uint16_t tile[64][kHeadDim + 2];
     const int gi = blockIdx.y;                          // (sequence, KV head)
     const int b = gi / p.Hkv;
     const int k0 = blockIdx.x * 64;
@@ -72,40 +68,26 @@ __global__ __launch_bounds__(256) void transpose_v_kernel(const PrefillProblem p
     // 64 keys x 128 d: thread reads 8 d of one key (16 bytes), 4 times
     for (int i = tid; i < 64 * 16; i += 256) {
         const int key = i >> 4, c = i & 15;
-        float f[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (k0 + key < S) {
-            const u32x4 w = *reinterpret_cast<const u32x4 *>(p.v + ((size_t)gi * p.Smax + k0 + key) * kHeadDim + 8 * c);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const half2_t h = as_h2(w[j]);
-                f[2 * j] = (float)h.x;
-                f[2 * j + 1] = (float)h.y;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) tile[key][8 * c + j] = f[j];
-    }
-    __syncthreads();
-    // thread writes 8 keys of one d (16 bytes) to each of hi and lo, 4 times; consecutive threads
-    // take consecutive d, which are consecutive 16-byte pieces of the tiled layout
-    for (int i = tid; i < kHeadDim * 8; i += 256) {
-        const int d = i & (kHeadDim - 1), kc = i >> 7;
-        unsigned hi[4], lo[4];
+        u32x4 w = {0u, 0u, 0u, 0u};
+        if (k0 + key < S) w = *reinterpret_cast<const u32x4 *>(p.v + ((size_t)gi * p.Smax + k0 + key) * kHeadDim + 8 * c);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            unsigned h2[2], l2[2];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const float x = tile[8 * kc + 2 * j + e][d];
-                h2[e] = bf16_bits(x);
-                l2[e] = bf16_bits(x - bf16_value(h2[e]));         // exact difference; fp16 = hi + lo exactly
-            }
-            hi[j] = h2[0] | (h2[1] << 16);
-            lo[j] = l2[0] | (l2[1] << 16);
+            const uint32_t x = w[j];
+            tile[key][8 * c + 2 * j] = (uint16_t)(x & 0xffffu);
+            tile[key][8 * c + 2 * j + 1] = (uint16_t)(x >> 16);
         }
+    }
+    __syncthreads();
+    // thread writes 8 keys of one d (16 bytes), 4 times; consecutive threads take consecutive d,
+    // which are consecutive 16-byte pieces of the tiled layout
+    for (int i = tid; i < kHeadDim * 8; i += 256) {
+        const int d = i & (kHeadDim - 1), kc = i >> 7;
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = (uint32_t)tile[8 * kc + 2 * j][d] | ((uint32_t)tile[8 * kc + 2 * j + 1][d] << 16);
         const size_t at = (size_t)gi * kHeadDim * p.Spad + vt_offset(k0 + 8 * kc, d);
-        *reinterpret_cast<u32x4 *>(p.vt_hi + at) = u32x4{hi[0], hi[1], hi[2], hi[3]};
-        *reinterpret_cast<u32x4 *>(p.vt_lo + at) = u32x4{lo[0], lo[1], lo[2], lo[3]};
+        *reinterpret_cast<u32x4 *>(p.vt + at) = u32x4{o[0], o[1], o[2], o[3]};
     }
 }
 
@@ -132,9 +114,8 @@ __device__ __forceinline__ void load_to_lds(const void *global, void *lds_base)
 constexpr int kKStride = 256;    // bytes per K row in LDS (16 chunks of 16 bytes, XOR-swizzled)
 struct PrefillLds {
     alignas(16) unsigned char k[2][kStep * kKStride];          // 2 x 8 KiB
-    alignas(16) unsigned char vh[2][4 * kHeadDim * 16];        // 2 x 8 KiB: [8-key chunk g][d][16 bytes], unit = d % 16
-    alignas(16) unsigned char vl[2][4 * kHeadDim * 16];        // 2 x 8 KiB
-    int bad[4];
+    alignas(16) unsigned char v[2][4 * kHeadDim * 16];         // 2 x 8 KiB: [8-key chunk g][d][16 bytes], unit = d % 16
+    int bad[4], redo[4];
 };
 // V^T: the 16 bytes of keys 8g .. 8g + 7 of row d
 __device__ __forceinline__ int v_slot(int d, int g) { return (g * kHeadDim + d) << 4; }
@@ -148,12 +129,11 @@ __device__ __forceinline__ int k_slot(int r, int c)
     return r * kKStride + ((c ^ ((r & 3) | (((r >> 3) & 3) << 2))) << 4);
 }
 
-// P3: the weights go to the matrix cores as THREE bf16 pieces (all 24 bits of the fp32 value; five
-// products per tile) instead of two (16 bits; three products).  Used for the first query tile
-// only: two pieces leave up to 2^-18 * |v| on an output element, which shows against the
-// relative tolerance only where a query sees so few keys that its terms can cancel to near zero
-// without the rounding errors averaging out -- the queries of the first tile.
-template <bool ONLINE, bool P3>
+// One 128-query tile.  ONLINE == false: unified scaling factor (Eq. 4); returns true when the tile
+// has to be redone with the synchronized scheme -- its guard fired (recorded in tile_flags) or a
+// weight left the range of the fp16 operands (not recorded: the result is the same either way).
+// ONLINE == true: the synchronized scheme (running maximum per query, Eq. 2); always stores.
+template <bool ONLINE>
 __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &lds, int b, int hq, int i0, int S)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -162,11 +142,14 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     const size_t kv_head = (size_t)b * p.Hkv + hkv;
     const uint16_t *qbase = p.q + (((size_t)b * p.Hq + hq) * p.Smax) * kHeadDim;
     const uint16_t *kbase = p.k + kv_head * p.Smax * kHeadDim;
-    const uint16_t *vh = p.vt_hi + kv_head * kHeadDim * p.Spad;
-    const uint16_t *vl = p.vt_lo + kv_head * kHeadDim * p.Spad;
+    const uint16_t *vt = p.vt + kv_head * kHeadDim * p.Spad;
     const float c1 = p.scale * kLog2e, c0 = -p.phi * kLog2e;      // log2 of e^{s x - phi} = c1 x + c0
     const float lo2 = p.lo * kLog2e, hi2 = p.hi * kLog2e;
     const int w0 = i0 + kWaveQ * wave;                       // first query of this wavefront
+    // -1.0 in a register the compiler cannot see through: keeps e - (float)hi a single mixed-precision
+    // fused multiply-add (fp16 operand read in place) instead of a conversion and a subtraction
+    float neg1;
+    asm("v_mov_b32 %0, -1.0" : "=v"(neg1));
 
     // Q^T as the B operand: lane (n, g) holds d = 32 kb + 8g .. +7 of query w0 + 16 qb + n
     f16x8 qB[kQB][4];
@@ -185,9 +168,11 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     float den[kQB], mrun[kQB];
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) { den[qb] = 0.f; mrun[qb] = -INFINITY; }
-    float zlo[kQB], zhi[kQB];                                  // running extremes of log2 e^{x - phi} (guard)
+    // unified scheme: running extremes of log2 of the SCALED weights (guard, fp16 range) and the
+    // queries' scale exponents k_q, folded into the additive constant of the logit
+    float zlo[kQB], zhi[kQB], kq[kQB], c0q[kQB];
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) { zlo[qb] = INFINITY; zhi[qb] = -INFINITY; }
+    for (int qb = 0; qb < kQB; ++qb) { zlo[qb] = INFINITY; zhi[qb] = -INFINITY; kq[qb] = 0.f; c0q[qb] = c0; }
 
     // key steps: the workgroup walks 0 .. nsteps - 1 (keys some query of the tile sees); this
     // wavefront computes while a key of the step is visible to one of its queries
@@ -199,8 +184,8 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
     // Cooperative tile fetch, global memory straight into LDS (no staging registers): a wavefront's
     // load instruction fills 1 KiB of LDS, lane l the 16 bytes at l * 16 from the wavefront's base,
     // each lane from a global address of its own.  Thread t moves chunks t and t + 256 of each of
-    // the K, V^T hi and V^T lo tiles.  The V^T tiles in memory are images of the LDS tiles; for K
-    // the lane whose LDS slot is (row r, physical chunk c') fetches logical chunk c' ^ key(r).
+    // the K and V^T tiles.  The V^T tile in memory is the image of the LDS tile; for K the lane
+    // whose LDS slot is (row r, physical chunk c') fetches logical chunk c' ^ key(r).
     auto fetch = [&](int s, int buf) {
         const int k0 = s * kStep;
 #pragma unroll
@@ -211,57 +196,34 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             const uint16_t *gk = kbase + (size_t)min(k0 + r, p.Smax - 1) * kHeadDim + 8 * c;
             const size_t at = (size_t)s * (kStep * kHeadDim) + 8 * id;
             load_to_lds(gk, &lds.k[buf][base]);
-            load_to_lds(vh + at, &lds.vh[buf][base]);
-            load_to_lds(vl + at, &lds.vl[buf][base]);
+            load_to_lds(vt + at, &lds.v[buf][base]);
         }
     };
     // the loads of this wavefront have landed in LDS
     auto fetched = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
-    // scores -> weights (bf16 hi / lo B operands) for one query block; log2 domain
-    auto weights = [&](auto masked, int qb, const f32x4 (&sc)[2], bf16x8 &pB, bf16x8 &pBl, bf16x8 &pBm, int k0) {
+    // scores -> weights (fp16 hi / lo B operands) for one query block; log2 domain
+    auto weights = [&](auto masked, bool first, int qb, const f32x4 (&sc)[2], f16x8 &pB, f16x8 &pBl, int k0) {
         constexpr bool MASKED = decltype(masked)::value;
         const int qrow = w0 + 16 * qb + n;
         float z[8];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][r], c1, c0);
-        float zmax = 0.f;
-        if constexpr (ONLINE) {
-            if constexpr (MASKED) {
-                const int kmax = qrow < S ? qrow : -1;                   // last key this query sees
+            for (int r = 0; r < 4; ++r) z[4 * t + r] = __builtin_fmaf(sc[t][r], c1, c0q[qb]);
+        bool ok[8];
 #pragma unroll
-                for (int j = 0; j < 8; ++j) z[j] = k0 + 8 * g + j <= kmax ? z[j] : -INFINITY;   // weight 0
+        for (int j = 0; j < 8; ++j) ok[j] = true;
+        if constexpr (MASKED) {
+            const int kmax = qrow < S ? qrow : -1;                       // last key this query sees
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                ok[j] = k0 + 8 * g + j <= kmax;                          // j = 4t + r: key k0 + 8g + j
+                z[j] = ok[j] ? z[j] : -INFINITY;                         // weight 0
             }
-            zmax = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
-        } else {
-            // Guard: running extremes of x - phi over all keys of the query, compared with the bounds
-            // once, after the last step (three-input min / max: four instructions each per block).
-            float zl[8];
-            if constexpr (MASKED) {
-                const int kmax = qrow < S ? qrow : -1;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const bool ok = k0 + 8 * g + j <= kmax;              // j = 4t + r: key k0 + 8g + j
-                    zl[j] = ok ? z[j] : INFINITY;
-                    z[j] = ok ? z[j] : -INFINITY;                        // weight 0
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 8; ++j) zl[j] = z[j];
-            }
-            float hi_run = zhi[qb], lo_run = zlo[qb];
-#pragma unroll
-            for (int j = 0; j < 8; j += 2) {
-                hi_run = fmaxf(fmaxf(z[j], z[j + 1]), hi_run);
-                lo_run = fminf(fminf(zl[j], zl[j + 1]), lo_run);
-            }
-            zhi[qb] = hi_run;
-            zlo[qb] = lo_run;
         }
         float shift = 0.f;
         if constexpr (ONLINE) {
-            float m = zmax;
+            float m = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
             m = fmaxf(m, __shfl_xor(m, 16));
             m = fmaxf(m, __shfl_xor(m, 32));
             const float mnew = fmaxf(mrun[qb], m);
@@ -273,33 +235,44 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
                 mrun[qb] = mnew;
             }
             shift = mnew == -INFINITY ? 0.f : mnew;
+        } else {
+            if (first) {
+                // The query's scale: its largest weight of this first step becomes 2^kFirstStepLog2.
+                // The four lane groups of a query hold different keys: they agree on the maximum first.
+                float m = fmaxf(fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3])), fmaxf(fmaxf(z[4], z[5]), fmaxf(z[6], z[7])));
+                m = fmaxf(m, __shfl_xor(m, 16));
+                m = fmaxf(m, __shfl_xor(m, 32));
+                const float k = (m == -INFINITY || m != m) ? 0.f : kFirstStepLog2 - m;      // no visible key, or NaN: leave as is
+                kq[qb] = k;
+                c0q[qb] = c0 + k;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) z[j] += k;
+            }
+            // Guard: running extremes over all keys of the query, compared with the bounds (shifted by
+            // k_q) once, after the last step (three-input min / max: four instructions each per step).
+            float hi_run = zhi[qb], lo_run = zlo[qb];
+#pragma unroll
+            for (int j = 0; j < 8; j += 2) {
+                hi_run = fmaxf(fmaxf(z[j], z[j + 1]), hi_run);
+                lo_run = fminf(fminf(ok[j] ? z[j] : INFINITY, ok[j + 1] ? z[j + 1] : INFINITY), lo_run);
+            }
+            zhi[qb] = hi_run;
+            zlo[qb] = lo_run;
         }
-        unsigned hi[4], lo[4], mid[4] = {0u, 0u, 0u, 0u};
+        unsigned hi[4], lo[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            f32x2 e = {__builtin_amdgcn_exp2f(z[2 * j] - shift), __builtin_amdgcn_exp2f(z[2 * j + 1] - shift)};
-            den[qb] += e[0] + e[1];
-            if constexpr (P3) {
-                // three pieces by truncation: hi = the upper 16 bits of e, mid = the upper 16 bits of
-                // what that leaves (exact in fp32), lo = the rest (at most 8 significant bits: exact)
-                // (the elements are taken by value first: bit-casting a vector element in place is unreliable)
-                const float e0 = e[0], e1 = e[1];
-                const unsigned t0 = __builtin_bit_cast(unsigned, e0), t1 = __builtin_bit_cast(unsigned, e1);
-                const float r0 = e0 - __builtin_bit_cast(float, t0 & 0xffff0000u), r1 = e1 - __builtin_bit_cast(float, t1 & 0xffff0000u);
-                const unsigned u0 = __builtin_bit_cast(unsigned, r0), u1 = __builtin_bit_cast(unsigned, r1);
-                const float w0 = r0 - __builtin_bit_cast(float, u0 & 0xffff0000u), w1 = r1 - __builtin_bit_cast(float, u1 & 0xffff0000u);
-                hi[j] = (t0 >> 16) | (t1 & 0xffff0000u);
-                mid[j] = (u0 >> 16) | (u1 & 0xffff0000u);
-                lo[j] = (__builtin_bit_cast(unsigned, w0) >> 16) | (__builtin_bit_cast(unsigned, w1) & 0xffff0000u);
-            } else {
-                hi[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e, bf16x2));
-                const f32x2 top = {__builtin_bit_cast(float, hi[j] << 16), __builtin_bit_cast(float, hi[j] & 0xffff0000u)};
-                lo[j] = __builtin_bit_cast(unsigned, __builtin_convertvector(e - top, bf16x2));        // e - top is exact
-            }
+            const float e0 = __builtin_amdgcn_exp2f(z[2 * j] - shift), e1 = __builtin_amdgcn_exp2f(z[2 * j + 1] - shift);
+            den[qb] += e0 + e1;
+            // hi = the weight cut to fp16 (11 bits), lo = what that leaves (exact in fp32) cut to fp16
+            const f16x2 h = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(e0, e1));
+            const _Float16 h0 = h.x, h1 = h.y;
+            const float l0 = __builtin_fmaf((float)h0, neg1, e0), l1 = __builtin_fmaf((float)h1, neg1, e1);
+            hi[j] = __builtin_bit_cast(unsigned, h);
+            lo[j] = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(l0, l1));
         }
-        pB = __builtin_bit_cast(bf16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
-        pBl = __builtin_bit_cast(bf16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
-        pBm = __builtin_bit_cast(bf16x8, u32x4{mid[0], mid[1], mid[2], mid[3]});
+        pB = __builtin_bit_cast(f16x8, u32x4{hi[0], hi[1], hi[2], hi[3]});
+        pBl = __builtin_bit_cast(f16x8, u32x4{lo[0], lo[1], lo[2], lo[3]});
     };
     // one step of this wavefront on the tiles in LDS buffer `buf`
     auto compute = [&](auto masked, int s, int buf) {
@@ -326,39 +299,26 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
 #pragma unroll
                 for (int qb = 0; qb < kQB; ++qb)
                     sc[qb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ka[t][kb]), qB[qb][kb], sc[qb][t], 0, 0, 0);
-        // O^T += V^T P^T with V = Vh + Vl and P = Ph + Pl: Vh Ph + Vl Ph + Vh Pl (Vl Pl is below fp32
-        // noise).  The A operands of tile dt + 1 are read from LDS while the MFMAs of tile dt run;
-        // those of tile 0 before the weights are computed.
-        u32x4 a_hi[kVAhead + 1], a_lo[kVAhead + 1];
-        auto read_v = [&](int dt, int slot) {
-            const int off = v_slot(16 * dt + n, g);
-            a_hi[slot] = *reinterpret_cast<const u32x4 *>(&lds.vh[buf][off]);
-            a_lo[slot] = *reinterpret_cast<const u32x4 *>(&lds.vl[buf][off]);
-        };
+        // O^T += V^T P^T with P = Ph + Pl: V Ph + V Pl.  The A operand of tile dt + 1 is read from LDS
+        // while the MFMAs of tile dt run; that of tile 0 before the weights are computed.
+        u32x4 a_v[kVAhead + 1];
+        auto read_v = [&](int dt, int slot) { a_v[slot] = *reinterpret_cast<const u32x4 *>(&lds.v[buf][v_slot(16 * dt + n, g)]); };
 #pragma unroll
         for (int dt = 0; dt < kVAhead; ++dt) read_v(dt, dt);
-        bf16x8 pB[kQB], pBl[kQB], pBm[kQB];
-        for (int qb = 0; qb < kQB; ++qb) weights(masked, qb, sc[qb], pB[qb], pBl[qb], pBm[qb], k0);
+        f16x8 pB[kQB], pBl[kQB];
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb) weights(masked, s == 0, qb, sc[qb], pB[qb], pBl[qb], k0);
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
             if (dt + kVAhead < 8) read_v(dt + kVAhead, (dt + kVAhead) % (kVAhead + 1));
-            const bf16x8 vh8 = __builtin_bit_cast(bf16x8, a_hi[dt % (kVAhead + 1)]), vl8 = __builtin_bit_cast(bf16x8, a_lo[dt % (kVAhead + 1)]);
+            const f16x8 v8 = __builtin_bit_cast(f16x8, a_v[dt % (kVAhead + 1)]);
 #pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pB[qb], acc[dt][qb], 0, 0, 0);
+            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(v8, pB[qb], acc[dt][qb], 0, 0, 0);
 #pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pB[qb], acc[dt][qb], 0, 0, 0);
-#pragma unroll
-            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBl[qb], acc[dt][qb], 0, 0, 0);
-            if constexpr (P3) {
-                // P = hi + mid + lo: + Vh Pm + Vl Pm (Vl Pl and below are under 2^-24 of a term)
-#pragma unroll
-                for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vh8, pBm[qb], acc[dt][qb], 0, 0, 0);
-#pragma unroll
-                for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vl8, pBm[qb], acc[dt][qb], 0, 0, 0);
-            }
-            // keep the order: the next tile's two LDS reads, then this tile's MFMAs
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, (P3 ? 5 : 3) * kQB, 0);
+            for (int qb = 0; qb < kQB; ++qb) acc[dt][qb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(v8, pBl[qb], acc[dt][qb], 0, 0, 0);
+            // keep the order: the next tile's LDS read, then this tile's four MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * kQB, 0);
         }
     };
 
@@ -385,15 +345,19 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
         den[qb] += __shfl_xor(den[qb], 16);
         den[qb] += __shfl_xor(den[qb], 32);
     }
-    // strict guard; a NaN logit (which the minimum and maximum skip) shows as a NaN denominator
-    bool bad = false;
+    if constexpr (!ONLINE) {
+        // strict guard on x - phi (the extremes carry the query's scale exponent); a NaN logit, which
+        // minimum and maximum skip, shows as a NaN denominator.  Apart from the guard: a weight at or
+        // beyond 2^kOverflowLog2 does not fit the fp16 operands.
+        bool bad = false, range = false;
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) bad |= (zhi[qb] >= hi2) | (zlo[qb] <= lo2) | (den[qb] != den[qb]);
-    const unsigned long long any = __ballot(bad);
-    if (lane == 0) lds.bad[wave] = any != 0ull;
-    __syncthreads();
-    const bool flagged = (lds.bad[0] | lds.bad[1] | lds.bad[2] | lds.bad[3]) != 0;
-    if (!ONLINE) {
+        for (int qb = 0; qb < kQB; ++qb) {
+            bad |= (zhi[qb] >= hi2 + kq[qb]) | (zlo[qb] <= lo2 + kq[qb]) | (den[qb] != den[qb]);
+            range |= zhi[qb] >= kOverflowLog2;
+        }
+        const unsigned long long any_bad = __ballot(bad), any_range = __ballot(range);
+        if (lane == 0) { lds.bad[wave] = any_bad != 0ull; lds.redo[wave] = (any_bad | any_range) != 0ull; }
+        __syncthreads();
         // one flag byte per 64 queries
         constexpr int kFlagTiles = kQTile / 64, kWavesPerFlag = 4 / kFlagTiles;
         if (tid < kFlagTiles) {
@@ -403,7 +367,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             for (int w = 0; w < kWavesPerFlag; ++w) f |= lds.bad[tid * kWavesPerFlag + w];
             if (t64 < p.tiles) p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + t64] = f != 0;
         }
-        if (flagged) return true;                        // uniform: the tile is redone, nothing stored
+        if ((lds.redo[0] | lds.redo[1] | lds.redo[2] | lds.redo[3]) != 0) return true;   // uniform: the tile is redone, nothing stored
     }
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb) {
@@ -422,7 +386,7 @@ __device__ __forceinline__ bool tile_all(const PrefillProblem &p, PrefillLds &ld
             *reinterpret_cast<uint2 *>(o + 16 * dt + 4 * g) = h;
         }
     }
-    return flagged;
+    return false;
 }
 
 __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillProblem p)
@@ -454,12 +418,9 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(const PrefillProblem p)
             p.tile_flags[((size_t)b * p.Hq + hq) * p.tiles + i0 / 64 + threadIdx.x] = 0;
         return;
     }
-    // the first query tile (queries that see 128 keys or fewer) carries its weights with all 24 bits
-    const bool flagged = i0 == 0 ? tile_all<false, true>(p, lds, b, hq, i0, S) : tile_all<false, false>(p, lds, b, hq, i0, S);
-    if (flagged) {                                       // Section 3 "Recomputation", for this tile
+    if (tile_all<false>(p, lds, b, hq, i0, S)) {         // Section 3 "Recomputation", for this tile
         __syncthreads();
-        if (i0 == 0) tile_all<true, true>(p, lds, b, hq, i0, S);
-        else tile_all<true, false>(p, lds, b, hq, i0, S);
+        tile_all<true>(p, lds, b, hq, i0, S);
     }
 }
 

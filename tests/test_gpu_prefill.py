@@ -130,6 +130,39 @@ def test_flagged_tiles_are_recomputed(H):
     close(H, got.reshape(-1, 128), want, "prefill with recomputation")
 
 
+@pytest.mark.parametrize("logit,phi,bounds", [(16.0, 3.0, (LO, HI)), (21.0, 3.0, (LO, HI)), (0.0, -16.8, (0.0, 23.3)),
+                                              (10.0, -16.8, (0.0, 40.0)), (-40.0, 3.0, (LO, HI))])
+def test_weights_beyond_the_fp16_operand_range_stay_exact_and_unflagged(H, logit, phi, bounds):
+    """The kernel hands its weights to the matrix cores as fp16 pairs under a per-query scale fixed after the
+    query's first 32 keys.  A later key whose weight exceeds that scale's headroom (2^11.9 above the first
+    step's maximum) while staying INSIDE the guard's bounds must not change what the caller sees: no flag (the
+    guard did not fire), and the exact result (the tile is redone with the synchronized scheme).  Cases: a key
+    13 .. 18 above the other logits; the paper's choice of phi at the lower end of the range (every exponent
+    positive, weights up to e^21), without and with such a key; and the opposite, first keys far ABOVE the
+    rest of the prompt (the later weights underflow the operands and are negligible, no redo needed)."""
+    B, Hq, Hkv, Smax = 1, 4, 4, 320
+    q, k, v, sl = draw(B, Hq, Hkv, Smax, [300], seed=7500)
+    scale = float(np.float32(1.0 / np.sqrt(128.0)))
+    u = np.zeros(128)
+    u[7] = 1.0
+    if logit == 0:
+        pass                                               # ordinary logits, only phi and the bounds differ
+    elif logit > 0:
+        pos = 150                                          # beyond the first key step of every query
+        q[0, 1, pos:300, 7] = np.float16(8.0)              # <q, u> = 8 for the later queries of head 1
+        k[0, 1, pos] = (logit * np.sqrt(128.0) / 8.0 * u).astype(np.float16)
+    else:
+        q[0, 1, :300, 7] = np.float16(8.0)                 # the first 32 keys carry +|logit| for every query of head 1
+        k[0, 1, :32, 7] = np.float16(-logit * np.sqrt(128.0) / 8.0)
+        phi = 3.0 - logit                                  # ... and phi sits above them: inside the bounds
+    rows = pf.all_rows(B, Hq, Smax)
+    want, flag, margin = pf.prefill_rows(q, k, v, sl, scale, rows, phi=phi, lo=bounds[0], hi=bounds[1], nthreads=8)
+    assert margin.min() > 1e-2 and not flag.any()          # inside (lo, hi): the guard stays quiet
+    got, tf = run_gpu(q, k, v, sl, scale, phi=phi, bounds=bounds)
+    assert not tf.any()
+    close(H, got.reshape(-1, 128), want, "weights beyond the fp16 operand range, logit %g phi %g" % (logit, phi))
+
+
 def test_nan_logit_flags_its_tiles(H):
     # a NaN inside a key of the prompt makes every logit against it NaN: the guard flags those
     # rows (a NaN is outside every range); rows before the key, and other heads, are untouched

@@ -152,7 +152,8 @@ struct ChunkLds {
 //                   chunk_flags and mloc = phi (the reference the sums are scaled by).
 //   SYNC == true  : the chunk's part of the synchronized partial softmax, Eq. 2:
 //                   m = max x, l = sum e^{x-m}, f.V = sum e^{x-m} v.  Writes num,
-//                   den, mloc = m and leaves chunk_flags alone.
+//                   den, mloc = m and leaves chunk_flags alone; `sync_flag` is what the
+//                   slot's record tells the row epilogue about the guard.
 // UP = groups of 4 keys per wavefront per pipeline stage.
 // Returns (uniformly over the workgroup) whether the guard fired (false for SYNC).
 // Pins the kernel arguments the chunk loop needs into scalar registers at this point,
@@ -237,7 +238,8 @@ template <bool PAGED> struct KvRows {
 // path of a short launch; a padding chunk then reads one block for nothing, so
 // large ragged launches leave it off.
 template <int C, int NW, int UP, bool SYNC, int XN, bool EARLY = false, bool PAGED = false>
-__device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds, int *len_out = nullptr)
+__device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, ChunkLds<NW, XN> &lds, int *len_out = nullptr,
+                                           int sync_flag = 1)
 {
     static_assert(!(EARLY && SYNC), "early loads belong to the unified scheme");
     static_assert(!(EARLY && PAGED), "the page table has to arrive before the first load");
@@ -492,7 +494,9 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         for (int i = 0; i < NW * 4; ++i) s += lds.den[i];
         store_coherent(&p.ws.den[slot], s);
         store_coherent(&p.ws.mloc[slot], mc);
-        store_meta(p, slot, s, mc, SYNC || flagged);       // a chunk is only recomputed because its guard fired
+        // the flag the row epilogue ORs into the row flag: the guard's; a recomputed chunk carries what its caller
+        // says (1 when the guard sent it here, 0 when it is redone for another reason)
+        store_meta(p, slot, s, mc, SYNC ? sync_flag : (int)flagged);
         if (!SYNC) p.ws.chunk_flags[slot] = flagged ? 1 : 0;
     }
     return flagged;

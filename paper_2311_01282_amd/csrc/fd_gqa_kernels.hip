@@ -9,22 +9,25 @@
 //            heads (zero rows), 4 instructions per block (d = 4 x 32).
 //   weights  P = e^{s S^T - phi} in fp32, in place in the accumulator layout
 //            (lane (head, g) holds keys g, 4+g, 8+g, 12+g of the block) -- Eq. 4, no maximum.
-//            fp16 cannot hold e^{x-phi} over the admissible range of x - phi and bf16 has
-//            8 significant bits, so P goes to the matrix cores as three bf16 pieces (hi + mid
-//            + lo = all 24 bits of the fp32 weight), and V, whose fp16 values have 11, as bf16
-//            hi + lo (exact):
+//            fp16 has neither the range of e^{x-phi} over the admissible x - phi nor, with 11
+//            bits, the precision, so P goes to the matrix cores as fp16 hi + lo pairs (22 bits)
+//            under a scale 2^k of the (wavefront, head)'s own: k, an integer, is fixed after the
+//            wavefront's first 16-key block so that the head's largest weight there lies in
+//            [2^3, 2^4]; it is constant over the keys the wavefront sums, so the sums of Eq. 4 stay
+//            plain sums, and it is taken out again (exactly: a power of two) before the
+//            wavefronts' tiles are added.  V is fp16 and is used as it is:
 //   P.V      out[head][d] += sum_key P[head][key] V[key][d]
-//            v_mfma_f32_16x16x16_bf16, five per tile (hi.hi + hi.lo + mid.hi + mid.lo + lo.hi;
-//            lo.lo is below 2^-24 of the term, so the sum is as good as an fp32 product --
-//            with two pieces of P, 2^-17 of a term, an output element that cancels to
-//            near zero in a sequence of a dozen keys missed the 1e-2 relative tolerance):
-//            A = P, whose four weights per lane are exactly contraction
-//            indices 4g..4g+3 when index 4g + r stands for key 4r + g; B = V, where lane
-//            (n, g) loads the 16 bytes d = 8n..8n+7 of the same keys 4r + g (r = 0..3) and
-//            feeds element e of the four rows to accumulator tile e (d = 8n + e), so V needs
-//            no transpose: 40 instructions per 16-key block, a fifth of the matrix-pipe
-//            time of the fp32 16x16x4 form, paid for with about 4 vector-ALU operations
-//            per V element for the split.
+//            v_mfma_f32_16x16x16_f16, two per tile (P_hi V + P_lo V): A = P, whose four weights
+//            per lane are exactly contraction indices 4g..4g+3 when index 4g + r stands for key
+//            4r + g; B = V, where lane (n, g) loads the 16 bytes d = 8n..8n+7 of the same keys
+//            4r + g (r = 0..3) and feeds element e of the four rows to accumulator tile e (d = 8n
+//            + e), so V needs no transpose, only a byte permute per pair of rows: 16 matrix
+//            instructions per 16-key block.  (Earlier forms: fp32 16x16x4, 32 instructions of 16
+//            passes; then bf16 with P in three and V in two pieces, 40 instructions and about 4
+//            vector-ALU operations per V element for the split.)
+//            A weight at or beyond 2^15.9 -- a logit more than 8 above the largest of the
+//            wavefront's first block -- does not fit: that (head, chunk) is redone on the per-row
+//            path like a flagged one, but without the flag.
 //
 // K reaches the A layout through a per-wavefront LDS tile (coalesced 1 KiB global
 // loads in, 16-byte reads out, XOR-swizzled so both directions are bank-conflict
@@ -51,39 +54,15 @@ struct GqaLds {
     float den[NW][64];
     float e_new[16];                 // weight of an appended key per head (0 when there is none)
     int   f_new[16];                 // ... and whether it left the bounds
-    unsigned long long bad[NW];
+    unsigned long long bad[NW], over[NW];
     int last;
 };
 
-typedef short bf16x4 __attribute__((ext_vector_type(4)));   // four bf16 bit patterns (an MFMA operand)
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-
-// Four floats as bf16 hi + lo: hi = the value truncated to bf16 (its upper 16 bits), lo = what
-// that leaves behind (exact in fp32) as bf16.  An fp16 value has 11 significant bits, so its lo
-// has at most 3 and truncation (EXACT_LO) loses nothing; otherwise lo is rounded to nearest and
-// hi + lo is the value to 2^-17 of its magnitude.
-template <bool EXACT_LO>
-__device__ __forceinline__ void split_bf16(const float (&x)[4], bf16x4 &hi, bf16x4 &lo)
-{
-    uint32_t t[4];
-    float u[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        t[i] = __builtin_bit_cast(uint32_t, x[i]);
-        u[i] = x[i] - __builtin_bit_cast(float, t[i] & 0xffff0000u);
-    }
-    // v_perm_b32: bytes 2, 3 of the second operand below bytes 2, 3 of the first
-    auto tops = [](float a, float b) { return __builtin_amdgcn_perm(__builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, a), 0x07060302u); };
-    auto nearest = [](float a, float b) { return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{a, b}, bf16x2)); };
-    hi = __builtin_bit_cast(bf16x4, make_uint2(__builtin_amdgcn_perm(t[1], t[0], 0x07060302u), __builtin_amdgcn_perm(t[3], t[2], 0x07060302u)));
-    if constexpr (EXACT_LO) {
-        lo = __builtin_bit_cast(bf16x4, make_uint2(tops(u[0], u[1]), tops(u[2], u[3])));
-    } else {
-        lo = __builtin_bit_cast(bf16x4, make_uint2(nearest(u[0], u[1]), nearest(u[2], u[3])));
-    }
-}
+constexpr float kFirstBlockLog2 = 4.f;    // a head's largest weight of the wavefront's first block lies in [2^3, 2^4] ...
+constexpr float kOverflowLog2 = 15.9f;    // ... and no later weight may reach 2^16 (fp16 ends at 65504)
 
 template <int C, bool PAGED = false, int NW = 4>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_kernel(const Problem p)
@@ -154,6 +133,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     float den = 0.f;
     bool bad = false;
     const bool head_on = n < G;
+    float kq = 0.f;                            // scale exponent of (this wavefront, head n), set by the first block
+    float zmax = -INFINITY;                    // largest log2 of a scaled weight of head n so far
+    float neg1;                                // -1.0 the compiler cannot fold: keeps e - (float)hi one mixed-precision FMA
+    asm("v_mov_b32 %0, -1.0" : "=v"(neg1));
 
     // Keys past the valid length re-read the last valid key and get weight zero.
     auto issue = [&](int blk, u32x4 (&kk)[4], u32x4 (&vv)[4]) {
@@ -172,7 +155,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
 #pragma unroll
         for (int r = 0; r < 4; ++r) vv[r] = load_stream(vp + at(min(k0 + 4 * r + g, last)));
     };
-    auto reduce = [&](int blk, const u32x4 (&kk)[4], const u32x4 (&vv)[4]) {
+    auto reduce = [&](int blk, bool first, const u32x4 (&kk)[4], const u32x4 (&vv)[4]) {
         const int k0 = blk * 16;
         // K block -> LDS row (4i + g), 16-byte slot n ^ row; then out in the A layout.
         // Row i of the A operand is key pk = 4(i%4) + i/4 of the block, so that score
@@ -195,54 +178,57 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
             const f16x8 ka = __builtin_bit_cast(f16x8, kst[pk * 16 + ((4 * kb + g) ^ pswz)]);
             sc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[kb], sc, 0, 0, 0);
         }
-        // sc[r] = <q_head n, k_key>, key = k0 + 4r + g.  Guard, then e^{x - phi}.
+        // sc[r] = <q_head n, k_key>, key = k0 + 4r + g.  Guard on x - phi, then the scaled weight.
+        float dd[4];
+        bool valid[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            valid[r] = k0 + 4 * r + g <= last;
+            dd[r] = sc[r] * scale + nphi;
+            bad |= valid[r] & head_on & !((dd[r] > lo) & (dd[r] < hi));
+        }
+        if (first) {
+            // the head's scale: the four lane groups of a head hold different keys and agree on the maximum first
+            float m = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) m = fmaxf(m, valid[r] ? dd[r] * kLog2e : -INFINITY);
+            m = fmaxf(m, __shfl_xor(m, 16));
+            m = fmaxf(m, __shfl_xor(m, 32));
+            kq = m > -INFINITY ? kFirstBlockLog2 - ceilf(m) : 0.f;      // (no finite logit: the guard has fired anyway)
+        }
         float pw[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const bool valid = k0 + 4 * r + g <= last;
-            const float d = sc[r] * scale + nphi;
-            bad |= valid & head_on & !((d > lo) & (d < hi));
-            const float e = __builtin_amdgcn_exp2f(d * kLog2e);
-            pw[r] = valid ? e : 0.f;
+            const float z = __builtin_fmaf(dd[r], kLog2e, kq);
+            zmax = fmaxf(zmax, valid[r] ? z : -INFINITY);
+            const float e = __builtin_amdgcn_exp2f(z);
+            pw[r] = valid[r] ? e : 0.f;
             den += pw[r];
         }
         // P as the A operand of the 16x16x16 product: lane (head n, g) holds contraction indices
         // 4g .. 4g+3, which stand for keys g, 4+g, 8+g, 12+g -- its own four weights.
-        // Three bf16 pieces carry a weight's 24 bits: hi and mid by truncation, lo what is left.
-        bf16x4 p_hi, p_mid, p_lo, unused;
-        float rest[4];
-        split_bf16<true>(pw, p_hi, p_mid);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const float top = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, pw[r]) & 0xffff0000u);
-            const float below = pw[r] - top;                                  // exact
-            rest[r] = below - __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, below) & 0xffff0000u);   // exact
-        }
-        split_bf16<false>(rest, p_lo, unused);       // rest has at most 8 significant bits: p_lo is exact, its own rest zero
+        // hi = the weight cut to fp16, lo = what that leaves (exact in fp32) cut to fp16: 22 bits.
+        const f16x2 h01 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(pw[0], pw[1]));
+        const f16x2 h23 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(pw[2], pw[3]));
+        const _Float16 h0 = h01.x, h1 = h01.y, h2 = h23.x, h3 = h23.y;
+        const float l0 = __builtin_fmaf((float)h0, neg1, pw[0]), l1 = __builtin_fmaf((float)h1, neg1, pw[1]);
+        const float l2 = __builtin_fmaf((float)h2, neg1, pw[2]), l3 = __builtin_fmaf((float)h3, neg1, pw[3]);
+        const f16x4 p_hi = __builtin_bit_cast(f16x4, make_uint2(__builtin_bit_cast(unsigned, h01), __builtin_bit_cast(unsigned, h23)));
+        const f16x4 p_lo = __builtin_bit_cast(f16x4, make_uint2(__builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(l0, l1)),
+                                                              __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(l2, l3))));
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-            // dword w of the four V rows: elements d = 8n + 2w (low halves) and 8n + 2w + 1 (high halves)
-            float even[4], odd[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const half2_t h = as_h2(vv[r][w]);
-                even[r] = (float)h.x;
-                odd[r] = (float)h.y;
-            }
-            bf16x4 e_hi, e_lo, o_hi, o_lo;
-            split_bf16<true>(even, e_hi, e_lo);
-            split_bf16<true>(odd, o_hi, o_lo);
-            // smallest products first; (p_lo . V_lo is below 2^-24 of the term)
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, e_hi, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_lo, o_hi, acc[2 * w + 1], 0, 0, 0);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, e_lo, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, o_lo, acc[2 * w + 1], 0, 0, 0);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, e_hi, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_mid, o_hi, acc[2 * w + 1], 0, 0, 0);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_lo, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_lo, acc[2 * w + 1], 0, 0, 0);
-            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, e_hi, acc[2 * w], 0, 0, 0);
-            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(p_hi, o_hi, acc[2 * w + 1], 0, 0, 0);
+            // dword w of the four V rows holds elements d = 8n + 2w (low halves) and 8n + 2w + 1 (high
+            // halves): the B operands of accumulator tiles 2w and 2w + 1 are the low, resp. high, halves
+            // of rows 0..3 (v_perm_b32: two halves of two registers into one)
+            const uint32_t v0 = vv[0][w], v1 = vv[1][w], v2 = vv[2][w], v3 = vv[3][w];
+            const f16x4 b_even = __builtin_bit_cast(f16x4, make_uint2(__builtin_amdgcn_perm(v1, v0, 0x05040100u), __builtin_amdgcn_perm(v3, v2, 0x05040100u)));
+            const f16x4 b_odd = __builtin_bit_cast(f16x4, make_uint2(__builtin_amdgcn_perm(v1, v0, 0x07060302u), __builtin_amdgcn_perm(v3, v2, 0x07060302u)));
+            // the small product first
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_lo, b_even, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_lo, b_odd, acc[2 * w + 1], 0, 0, 0);
+            acc[2 * w] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_hi, b_even, acc[2 * w], 0, 0, 0);
+            acc[2 * w + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(p_hi, b_odd, acc[2 * w + 1], 0, 0, 0);
         }
     };
     // This wavefront's blocks are wave, wave + NW, ...; nmine of them hold a valid key.
@@ -257,18 +243,27 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
         for (; i + 2 < nmine; i += 2) {
             issue(wave + NW * (i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of the arithmetic
-            reduce(wave + NW * i, kA, vA);
+            reduce(wave + NW * i, i == 0, kA, vA);
             issue(wave + NW * (i + 2), kA, vA);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + NW * (i + 1), kB, vB);
+            reduce(wave + NW * (i + 1), false, kB, vB);
         }
         if (i + 2 == nmine) {
             issue(wave + NW * (i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + NW * i, kA, vA);
-            reduce(wave + NW * (i + 1), kB, vB);
+            reduce(wave + NW * i, i == 0, kA, vA);
+            reduce(wave + NW * (i + 1), false, kB, vB);
         } else {
-            reduce(wave + NW * i, kA, vA);
+            reduce(wave + NW * i, i == 0, kA, vA);
+        }
+        // Take the scales out again (exact: integer powers of two).  den belongs to head n; acc[e][r]
+        // to head 4g + r, whose exponent sits in the lanes with n = 4g + r.
+        den *= __builtin_amdgcn_exp2f(-kq);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float inv = __builtin_amdgcn_exp2f(-__shfl(kq, 4 * g + r));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e][r] *= inv;
         }
     }
 
@@ -297,6 +292,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
 
     // ---- workgroup reduction and publication of the G rows' partial results ----
     const unsigned long long bad_mask = __ballot(bad);
+    const unsigned long long over_mask = __ballot(head_on & (zmax >= kOverflowLog2));   // a weight beyond the fp16 operand
     __syncthreads();                           // every wavefront is done with its K staging
     // acc[e][r] is (head 4g + r, d = 8n + e) of this wavefront's partial tile.
 #pragma unroll
@@ -311,16 +307,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
         }
     }
     lds.den[wave][lane] = den;
-    if (lane == 0) lds.bad[wave] = bad_mask;
+    if (lane == 0) { lds.bad[wave] = bad_mask; lds.over[wave] = over_mask; }
     if (n == 0 && wave < 4) { lds.e_new[4 * wave + g] = e_new; lds.f_new[4 * wave + g] = f_new; }
     __syncthreads();
-    unsigned long long any = 0;
+    unsigned long long any = 0, any_over = 0;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) any |= lds.bad[w];
+    for (int w = 0; w < NW; ++w) { any |= lds.bad[w]; any_over |= lds.over[w]; }
     // head h was flagged iff one of its 4 lanes (h, h+16, h+32, h+48) in any wavefront says so
     unsigned flagged_heads = (unsigned)((any | (any >> 16) | (any >> 32) | (any >> 48)) & 0xffffull);
 #pragma unroll
     for (int h = 0; h < 16; ++h) flagged_heads |= (unsigned)(lds.f_new[h] != 0) << h;
+    // heads whose sums have to be redone: the flagged ones, and those with a weight that did not fit
+    const unsigned redo_heads = flagged_heads | (unsigned)((any_over | (any_over >> 16) | (any_over >> 32) | (any_over >> 48)) & 0xffffull);
     auto den_of = [&](int h) {                 // Eq. 4's denominator of head h over this chunk
         float s = lds.e_new[h];
 #pragma unroll
@@ -332,7 +330,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     // A sequence of one chunk whose guard stayed quiet is complete here: its rows' results are
     // this workgroup's own sums, so they go out directly instead of through the workspace and
     // the epilogue (same arithmetic: the epilogue's factors are exactly 1 for such a row).
-    const bool solo = p.elect && nb == 1 && !flagged_heads;
+    const bool solo = p.elect && nb == 1 && !redo_heads;
     // 4 consecutive elements per thread: one 16-byte LDS read per wavefront tile, 16 bytes out
     for (int i = 4 * tid; i < G * kHeadDim; i += 4 * kGqaThreads) {
         float4 o = *reinterpret_cast<const float4 *>(&lds.tile[i]);
@@ -377,13 +375,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     if (solo) return;
 
     // Section 3 "Recomputation": a (head, chunk) whose guard fired is redone with the
-    // synchronized scheme on the per-row path (rare; re-reads this chunk only).
-    if (flagged_heads) {
+    // synchronized scheme on the per-row path (rare; re-reads this chunk only).  So is one whose
+    // weights did not fit the fp16 operands; its slot record then says "not flagged".
+    if (redo_heads) {
         wait_stores_performed();               // the stores above must not overtake the rewrite
         for (int h = 0; h < G; ++h) {
-            if (!((flagged_heads >> h) & 1)) continue;
+            if (!((redo_heads >> h) & 1)) continue;
             __syncthreads();
-            chunk_body<C, NW, UP, true, C, false, PAGED>(p, row0 + h, c, *reinterpret_cast<ChunkLds<NW, C> *>(lds.tile));
+            chunk_body<C, NW, UP, true, C, false, PAGED>(p, row0 + h, c, *reinterpret_cast<ChunkLds<NW, C> *>(lds.tile), nullptr,
+                                                         (int)((flagged_heads >> h) & 1));
         }
     }
 

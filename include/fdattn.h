@@ -171,8 +171,12 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
  * together so each K and V element is read from memory once per group.
  * Requires 2 <= n_q_heads / n_kv_heads <= 16.  (Grouping is not in the paper;
  * per query head the arithmetic is Eq. 4 unchanged: the weights e^{x-phi} are formed
- * in fp32 and enter the second product with all 24 bits, as three bf16 pieces on the
- * matrix cores.)  Flags are per query head.
+ * in fp32 and enter the second product on the matrix cores as fp16 hi + lo pairs, 22
+ * significant bits, under a power-of-two scale per head that is taken out again
+ * exactly; V is used as it is.  A (head, chunk) with a weight beyond the range of
+ * that operand -- a logit more than 8 above the largest among the first keys of its
+ * part of the chunk -- is recomputed like a flagged one, in fp32 throughout, without
+ * raising a flag.)  Flags are per query head and report the guard alone.
  * Requires fd_workspace_init.
  */
 fd_status fd_decode_attn_gqa(const fd_shape *shape, const void *q, const void *k_cache,

@@ -21,7 +21,7 @@ def exact(oracle, case):
 
 def num_bound(case, oden):
     """Error bound of a chunk's numerator sum_k P_k V_k: the kernel feeds P to the matrix cores as
-    three bf16 pieces (all 24 bits of the fp32 weight; V's split is exact), accumulates in fp32 and
+    fp16 hi + lo pairs (22 bits of the fp32 weight; V is fp16 as it is), accumulates in fp32 and
     computes P itself in fp32 (a few 1e-6 relative): 1e-5 * sum_k P_k |V_k|, bounded here by the
     chunk's denominator times the largest |V|."""
     return 1e-5 * np.abs(case["v"].astype(np.float64)[np.isfinite(case["v"])]).max() * oden
@@ -146,8 +146,8 @@ def test_gqa_single_chunk_sequences_publish_partials_and_recompute(oracle, H):
 @pytest.mark.parametrize("phi", [40.0, -15.0])
 def test_gqa_weights_at_both_ends_of_the_admissible_range(oracle, H, phi):
     """Every weight e^{x - phi} near e^-40 (phi = 40) or near e^+15 (phi = -15): inside the bounds, so
-    nothing is flagged, and far outside what fp16 could hold -- the matrix-core operands (bf16 hi + lo)
-    must carry them; one key per sequence dominates its row as well."""
+    nothing is flagged, and far outside what fp16 could hold -- the matrix-core operands (fp16 pairs under a
+    scale of the head's own) must carry them; one key per sequence dominates its row as well."""
     case = synth.make_case(B=2, Hq=16, Hkv=2, D=128, Smax=1500, seed=440, seq_lens=[1500, 700], poison_padding=True)
     synth.plant_keys(case, 2, 4.5, seed=441, allow_shared_kv=True)       # logit about 4.5: inside the bounds for both phi
     want = exact(oracle, case)
@@ -160,3 +160,26 @@ def test_gqa_weights_at_both_ends_of_the_admissible_range(oracle, H, phi):
     assert not cf.any() and not rf.any() and n == 0
     # and through the per-row kernel, whose arithmetic is fp32 throughout
     assert np.abs(got - dc.run("fd_decode_attn", phi=phi)).max() <= 1e-3
+
+
+@pytest.mark.parametrize("gamma,chunk", [(14.0, 512), (17.0, 2048), (14.0, 64)])
+def test_gqa_weights_beyond_the_fp16_operand_range_stay_exact_and_unflagged(oracle, H, gamma, chunk):
+    """The grouped kernel hands its weights to the matrix cores as fp16 pairs under a scale fixed after each
+    wavefront's first 16 keys.  A later key whose logit is 10 .. 18 above the rest, yet INSIDE the bounds, does
+    not fit that scale: its (head, chunk) must be redone on the per-row path -- exact result, and no flag, for
+    the guard did not fire.  (Where the key falls into a wavefront's first block the scale adapts instead.)"""
+    case = synth.make_case(B=3, Hq=16, Hkv=2, D=128, Smax=2048, seed=450, seq_lens=[2048, 1300, 90], poison_padding=True)
+    planted = synth.plant_keys(case, 8, gamma, seed=451 + chunk, allow_shared_kv=True)
+    assert len(planted) == 8
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk)
+    assert margin.min() > 1e-2 and not orf.any()          # logit - phi about 7 .. 16: inside (-60, 20)
+    x = [float(case["q"][b, h].astype(np.float64) @ case["k"][b, h // 8, pos].astype(np.float64)) * case["scale"] for b, h, pos in planted]
+    assert min(x) > 9.5                                    # ... and 8 or more above every other logit of its row
+    dc = H.DeviceCase(case, chunk=chunk)
+    for _ in range(2):
+        got = dc.run("fd_decode_attn_gqa")
+        H.assert_close(got, want, "gqa, weights beyond the fp16 operand range")
+        cf, rf, n, rows = dc.flags()
+        assert not cf.any() and not rf.any() and n == 0
+    assert np.abs(got - dc.run("fd_decode_attn")).max() <= 1e-3

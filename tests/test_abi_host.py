@@ -239,6 +239,12 @@ def test_pick_chunk_fills_the_chip_when_the_shape_allows_it(fdattn):
                         # one round of the chip that is 90 % full beats two rounds when it needs at most 2/3 of the chunks
                         ((5, 64, 8, 3000), 512), ((30, 64, 8, 4096), 4096), ((1, 64, 8, 32768), 1024)):
         assert fdattn.fd_pick_chunk(fdattn.make_shape(*shape[:3], 128, shape[3], 0, 0.1)) == want, shape
+    # groups of more than 16 heads run on the per-row kernel (one workgroup per query head and chunk): the pick is
+    # the per-row one, not the grouped kernel's long chunks
+    for (B, Hq, Hkv, Smax) in [(1, 34, 2, 8192), (4, 40, 2, 4096), (1, 64, 1, 32768), (16, 32, 1, 4096)]:
+        assert Hq // Hkv > 16
+        assert (fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hkv, 128, Smax, 0, 0.1)) ==
+                fdattn.fd_pick_chunk(fdattn.make_shape(B, Hq, Hq, 128, Smax, 0, 0.1))), (B, Hq, Hkv, Smax)
     # invalid shapes give 0
     assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 32, 64, 8192, 256, 0.1)) == 0
     assert fdattn.fd_pick_chunk(fdattn.make_shape(1, 32, 5, 128, 8192, 256, 0.1)) == 0

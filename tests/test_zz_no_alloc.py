@@ -61,3 +61,32 @@ def test_static_limit_is_an_error_and_leaves_out_alone(H):
     assert e.value.status == fdattn.FD_ERR_STATIC_LIMIT
     torch.cuda.synchronize()
     assert torch.isnan(dc.out).all()             # nothing was enqueued
+
+
+def test_static_entry_under_stream_capture(oracle, H):
+    """What the entry point is for: a caller that records its step with a stream capture and may not allocate.
+    After one eager call (the first call on a device looks the array's address up), the call is captured,
+    replayed five times with eager calls of another shape in between (they share the one array), and every
+    replay must reproduce the eager result bit for bit."""
+    case = synth.make_case(B=2, Hq=8, Hkv=8, D=128, Smax=2048, seed=9800, seq_lens=[2048, 1500])
+    synth.plant_keys(case, 1, 36.0, seed=9801)
+    other = synth.make_case(B=1, Hq=16, Hkv=2, D=128, Smax=512, seed=9802, seq_lens=[400])
+    dc, dco = H.DeviceCase(case, chunk=256), H.DeviceCase(other, chunk=128)
+    want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=8)
+    eager = run_static(dc)
+    H.assert_close(eager, want, "eager")
+    side = torch.cuda.Stream(device=dc.dev)
+    graph = torch.cuda.CUDAGraph()
+    out_g = torch.full_like(dc.out, float("nan"))
+    side.wait_stream(torch.cuda.current_stream(dc.dev))
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fdattn.fd_decode_attn_static(*dc._args(), synth.PHI, synth.BOUNDS, out_g.data_ptr(), side.cuda_stream)
+    torch.cuda.synchronize(dc.dev)
+    for i in range(5):
+        out_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize(dc.dev)
+        assert np.array_equal(out_g.cpu().numpy().astype(np.float64), eager), "replay %d differs from the eager call" % i
+        run_static(dco)                                  # another shape through the same array between replays
+    del graph

@@ -136,8 +136,9 @@ fd_status make_problem(const fd_shape *sh, const void *q, const void *k, const v
     p->k_store = p->v_store = nullptr;
     p->block_table = nullptr;
     p->pages_per_seq = 0; p->page_shift = 0; p->n_pages = 0;
+    p->scatter = 0;
 #ifdef FD_PHASE_PROBE
-    p->scatter = g_probe_scatter;
+    p->scatter = g_probe_scatter;          // (probe build: spread the rows over the XCDs in every launch)
 #endif
     return FD_OK;
 }

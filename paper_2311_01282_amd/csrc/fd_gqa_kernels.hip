@@ -405,6 +405,7 @@ template <int C> struct GqaLauncher {
         if (grid == 0) return hipSuccess;
         Problem p = p0;
         p.chunk_major = grid <= 1024u;
+        p.scatter |= !p.elect;                     // no hand-over inside the launch: every XCD reads from every head group
         // 4 wavefronts per workgroup.  (8 were measured for launches of at most one workgroup per
         // compute unit: within 2 % either way at 256 workgroups, 12 % faster only for a lone
         // 4096-key chunk, which fd_pick_chunk never chooses.)

@@ -64,22 +64,25 @@ struct Problem {
     // page = 1 << page_shift.  Smax is the logical capacity pages_per_seq * page.
     const int32_t *block_table;
     int pages_per_seq, page_shift, n_pages;
-#ifdef FD_PHASE_PROBE
-    // Probe build only: 1 = deal the chunks of a row (head group) to DIFFERENT XCDs -- chunk c of row r
-    // to XCD (r + c) % 8 -- instead of all to XCD r % 8, so that every hand-over of the fused kernels
-    // crosses from one XCD's L2 to another's (tests of the hand-over's coherence; timing of its cost).
+    // Which XCD (workgroup index modulo 8) serves which row of a block of 8 rows (or head groups):
+    //   0: row r on XCD r % 8, all its chunks on that one XCD;
+    //   1: chunk c of row r on XCD (r + c) % 8 -- every XCD reads from every row.
+    // Set at launch: 1 for the launches that leave the row epilogue to a second launch (see
+    // row_slot below); the probe build can force 1 everywhere (tests of the hand-over).
     int scatter;
-#endif
 };
 
 // XCD slot (workgroup index modulo 8) -> the row, or head group, within its block of 8 that the
-// workgroup serves: the slot itself, or -- probe build, scatter on -- the slot rotated by the chunk.
+// workgroup serves: the slot itself, or the slot rotated by the chunk.  With rows on fixed XCDs an
+// XCD only ever reads addresses that agree in the bits just above the row stride, and for some row
+// strides (4096 keys = 1 MiB: a batch of 16 x 32 rows) the memory system then serves it from a part
+// of its channels only: 74 % of the HBM peak against 85 % with the rows spread (batch 16 x 4096
+// keys, 1024-key chunks; 4 x 16384: 81 -> 85 %; 1 x 65536: 79 -> 83 %; shapes that were fast stay
+// fast).  Launches that hand over between workgroups keep a row on one XCD (measured: no
+// difference there, and the counters of a row then live in one L2).
 __device__ __forceinline__ int row_slot(const Problem &p, int slot, int c)
 {
-#ifdef FD_PHASE_PROBE
-    if (p.scatter) return (slot - c) & 7;
-#endif
-    return slot;
+    return p.scatter ? (slot - c) & 7 : slot;
 }
 
 // Number of keys resident in the cache: the clamped entry of seq_lens.

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void partial_unified_kernel(const
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
     const int c = SMALL ? j / groups8 : j % p.nc;
-    const int row = (blockIdx.x & 7) + 8 * (SMALL ? j - c * groups8 : j / p.nc);
+    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (SMALL ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     chunk_body<C, NW, UP, false, 1, EARLY, false>(p, row, c, lds);
 }
@@ -226,6 +226,7 @@ template <int C> struct FusedLauncher {
         if (grid == 0) return hipSuccess;
         Problem p = p0;
         p.chunk_major = p.elect;                   // what the kernel compiles in (the grouped kernel reads the flag)
+        p.scatter |= !p.elect;                     // no hand-over inside the launch: every XCD reads from every row
         if (p.block_table)
             return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
                            : launch(decode_fused_kernel<C, false, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p);
@@ -237,10 +238,12 @@ template <int C> struct FusedLauncher {
 };
 
 template <int C> struct UnifiedLauncher {
-    static hipError_t run(const Problem &p, hipStream_t s)
+    static hipError_t run(const Problem &p0, hipStream_t s)
     {
-        const unsigned grid = (unsigned)(8ll * ((p.rows + 7) / 8) * p.nc);
+        const unsigned grid = (unsigned)(8ll * ((p0.rows + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
+        Problem p = p0;
+        p.scatter |= grid > 1024u;                 // as the fused kernel's launches of that size
         const dim3 block(Tune<C>::NW * 64);
         if (grid <= (unsigned)kComputeUnits) return launch(partial_unified_kernel<C, true, true>, dim3(grid), block, s, p);
         if (grid <= 1024u) return launch(partial_unified_kernel<C, true, false>, dim3(grid), block, s, p);

@@ -203,9 +203,12 @@ class Runner:
         nc = -(-wl.Smax // chunk)
         wgs = wl.B * (wl.Hkv if gqa else wl.Hq) * nc
         # the library's own rule: the grouped kernel finishes its rows itself up to 256 workgroups and 8 chunks
-        # per row, the per-row kernel up to 1024 workgroups; beyond, the row epilogue is a launch of its own
+        # per row, the per-row kernel up to 1024 workgroups unless the launch is long (more than 256 workgroups over
+        # 320 MiB or more of cache); beyond, the row epilogue is a launch of its own
         fused = entry in ("fd_decode_attn", "fd_decode_attn_gqa", "fd_decode_attn_static")
-        self.single_launch = fused and ((wgs <= 256 and nc <= 8) if gqa else wgs <= 1024)
+        cache_bytes = wl.B * wl.Hkv * wl.Smax * wl.D * 2 * 2
+        self.single_launch = fused and ((wgs <= 256 and nc <= 8) if gqa else
+                                        (wgs <= 1024 and (wgs <= 256 or cache_bytes < (320 << 20))))
         self.launches = 1 if self.single_launch else (3 if entry == "fd_decode_attn_multikernel" else 2)
         self.grid = (wl.B * wl.Hkv * nc) if gqa else 8 * ((wl.B * wl.Hq + 7) // 8) * nc
 

@@ -147,8 +147,9 @@ fd_status fd_workspace_init(const fd_shape *shape, fd_workspace ws, void *stream
  *      sums of Eq. 4, flagged rows by the synchronized update of Eq. 2 over all
  *      partial results, each rescaled from its own reference (phi, or the chunk
  *      maximum) to the row maximum of those references.  For grids of more than
- *      1024 workgroups (fd_decode_attn_gqa: more than 256 workgroups, or more than 8
- *      chunks per row) step 3 runs as a second, tiny
+ *      1024 workgroups, or of more than 256 workgroups over 320 MiB or more of cache
+ *      (fd_decode_attn_gqa: more than 256 workgroups, or more than 8 chunks per row)
+ *      step 3 runs as a second, tiny
  *      launch instead (one workgroup per row, no counters): large grids are
  *      throughput-bound and the election's two memory round trips per workgroup
  *      cost more than a launch.

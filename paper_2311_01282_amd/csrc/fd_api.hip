@@ -161,6 +161,18 @@ inline int elect_in_kernel(long long workgroups, long long limit = 1024, bool an
     return workgroups <= limit && and_also;
 }
 
+// The per-row kernel: one launch up to 1024 workgroups, unless the launch is long -- more than one
+// round of the chip over 320 MiB or more of cache -- where the second launch wins (whole call, one
+// launch / two, same box: 2 x 32 rows x 16384 keys 90.0 / 84.7 us, 4 x 32 x 8192 85.4 / 83.6, 1 x 32 x
+// 32768 91.3 / 83.7, 1 x 32 x 24000 68.9 / 65.0; at 256 MiB they tie: 44.7 / 44.5, 46.2 / 45.7, 46.3 /
+// 44.8) at the price of a cache that is mostly empty (1 x 32 x 32768 holding 8192 keys: 26.8 / 31.4 us).
+inline int elect_per_row(const fd::Problem &p)
+{
+    const long long workgroups = (long long)p.rows * p.nc;
+    const long long cache_bytes = (long long)p.B * p.Hkv * p.Smax * fd::kHeadDim * 2 * 2;
+    return elect_in_kernel(workgroups, 1024, workgroups <= 256 || cache_bytes < (320ll << 20));
+}
+
 // The grouped kernel: its elected workgroup finishes the G rows of its head group by itself,
 // walking each row's chunks in order, which is the cheaper way up to 8 chunks per row and 256
 // workgroups; beyond either the second launch (one workgroup per row, 8 chunk slices in
@@ -347,7 +359,7 @@ fd_status fd_decode_attn(const fd_shape *shape, const void *q, const void *k_cac
     if (st != FD_OK) return st;
     if (p.rows == 0) return FD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    p.elect = elect_in_kernel((long long)p.rows * p.nc);
+    p.elect = elect_per_row(p);
     FD_TRY(fd::launch_decode_fused(p, s));
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
     return FD_OK;
@@ -393,7 +405,7 @@ fd_status fd_decode_attn_append(const fd_shape *shape, const void *q, const void
         p.elect = elect_grouped(p);
         FD_TRY(fd::launch_decode_fused_gqa(p, s));
     } else {
-        p.elect = elect_in_kernel((long long)p.rows * p.nc);
+        p.elect = elect_per_row(p);
         FD_TRY(fd::launch_decode_fused(p, s));
     }
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));
@@ -425,7 +437,7 @@ static fd_status run_fused(fd::Problem &p, hipStream_t s)
         p.elect = elect_grouped(p);
         FD_TRY(fd::launch_decode_fused_gqa(p, s));
     } else {
-        p.elect = elect_in_kernel((long long)p.rows * p.nc);
+        p.elect = elect_per_row(p);
         FD_TRY(fd::launch_decode_fused(p, s));
     }
     if (!p.elect) FD_TRY(fd::launch_row_epilogue(p, s));

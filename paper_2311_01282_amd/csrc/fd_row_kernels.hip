@@ -45,25 +45,21 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     // go to the same XCD (row % 8), so the row's counters and partial results stay
     // in one L2 instead of bouncing between eight.  Placement only affects speed:
     // every hand-over below is device-coherent wherever the workgroups land.
-    // Order within that, chosen at launch:
-    //   a launch of up to 1024 workgroups goes chunk-major -- chunk 0 of every row, then chunk
-    //   1, ... -- so that the chunks past the end of the sequences (the launch covers max_seq)
-    //   are dispatched last and leave at once, instead of taking a compute unit's first slot
-    //   while another unit gets two full chunks (measured against row-major: 32.5 -> 25.8 us
-    //   for 8192 keys in a cache of 8208, 33.5 -> 29 us in a cache of 16384, 107 -> 89 us for
-    //   the grouped kernel on 32 sequences of 4096 keys in a cache of 8192);
-    //   a larger launch goes row-major: the dispatcher balances it as it goes, and the
-    //   workgroups in flight then cover whole rows -- every bit of the address below the row
-    //   stride -- where chunk-major confines a round of the chip to a slice of every row
-    //   (rows of a power-of-two stride: 8-10 % slower; the ragged batch of 16: 2 %).
-    // (For this kernel the two limits coincide -- in-kernel hand-over and chunk-major order both
-    // end at 1024 workgroups -- so the order is a compile-time choice: one division, not two.
-    // Multiply-shift quotients from precomputed reciprocals and a two-dimensional launch were
-    // both measured slower than this: c1 24.0 us against 23.75.)
+    // Order within that: row-major -- all chunks of rows 0..7, then of rows 8..15, ... -- except in
+    // the launches of at most one workgroup per compute unit (EARLY), which go chunk-major and whose
+    // order hardly matters (every workgroup is resident at once).  Chunk-major order -- chunk 0 of
+    // every row, then chunk 1, ... -- used to serve every launch of up to 1024 workgroups, because it
+    // dispatches the chunks past the end of the sequences last (8192 keys in a cache of 16384: 33.5 ->
+    // 29 us); but it confines a round of the chip to one slice of every row, and for rows of a
+    // power-of-two stride that costs up to 20 % on some boxes (2 x 32 rows of 8192 keys, 1024-key
+    // chunks: 54.3 us against 44.7 row-major on the same box; 1 x 32 rows of 16384 keys, 512-key chunks:
+    // 51.1 against 46.3; other boxes: 45.8 either way), where row-major with the in-kernel hand-over
+    // loses 4 % on the half-empty cache (24.2 -> 25.2 us, 25.9 -> 26.8 us at a quarter).
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int c = ELECT ? j / groups8 : j % p.nc;
-    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (ELECT ? j - c * groups8 : j / p.nc);
+    constexpr bool CM = EARLY;                 // chunk-major in the one-round launches only (see below)
+    const int c = CM ? j / groups8 : j % p.nc;
+    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (CM ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     FD_PHASE(0);
     int S;
@@ -103,8 +99,8 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
 
 // First launch of the literal chain: Eq. 4 inner sums and the range guard, nothing else (no
 // recomputation, no hand-over).  Same workgroup shape, workgroup order and early loads as the
-// fused kernel: SMALL = a launch of at most 1024 workgroups (chunk-major order), EARLY = of at
-// most 256 (first loads before the sequence length has arrived).
+// fused kernel: SMALL = a launch of at most 1024 workgroups (kernel arguments fetched in one batch),
+// EARLY = of at most 256 (chunk-major order, first loads before the sequence length has arrived).
 template <int C, bool SMALL, bool EARLY>
 __global__ __launch_bounds__(Tune<C>::NW * 64) void partial_unified_kernel(const Problem p)
 {
@@ -114,8 +110,8 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void partial_unified_kernel(const
     if constexpr (SMALL) fetch_arguments_now(p);
     const int groups8 = (p.rows + 7) >> 3;
     const int j = blockIdx.x >> 3;
-    const int c = SMALL ? j / groups8 : j % p.nc;
-    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (SMALL ? j - c * groups8 : j / p.nc);
+    const int c = EARLY ? j / groups8 : j % p.nc;              // the fused kernel's orders
+    const int row = row_slot(p, blockIdx.x & 7, c) + 8 * (EARLY ? j - c * groups8 : j / p.nc);
     if (row >= p.rows) return;
     chunk_body<C, NW, UP, false, 1, EARLY, false>(p, row, c, lds);
 }

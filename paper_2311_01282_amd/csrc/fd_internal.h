@@ -50,7 +50,7 @@ struct Problem {
     WsView ws;
     int B, Hq, Hkv, G, Smax, C, nc, rows;
     float scale, phi, lo, hi;
-    int chunk_major; // workgroup order of the fused kernels, set at launch: 1 = chunk 0 of every row, then chunk 1, ...
+    int chunk_major; // workgroup order of the grouped kernel, set at launch: 1 = chunk 0 of every row, then chunk 1, ...
     int elect;     // 1: chunk kernels elect a finisher per row and run the row epilogue themselves;
                    // 0: a separate row-epilogue launch follows (no per-workgroup hand-over latency)
     // Fused append (null otherwise): this step's K and V rows, [B, Hkv, D].  Sequence b then

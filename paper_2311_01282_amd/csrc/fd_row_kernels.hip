@@ -41,10 +41,11 @@ __global__ __launch_bounds__(Tune<C>::NW * 64) void decode_fused_kernel(const Pr
     __shared__ ChunkLds<NW, C> lds;
     const int tid = threadIdx.x;
     if constexpr (ELECT) fetch_arguments_now(p);
-    // Workgroups are dealt to the 8 XCDs round-robin by index.  All chunks of a row
-    // go to the same XCD (row % 8), so the row's counters and partial results stay
-    // in one L2 instead of bouncing between eight.  Placement only affects speed:
-    // every hand-over below is device-coherent wherever the workgroups land.
+    // Workgroups are dealt to the 8 XCDs round-robin by index.  In a launch that hands its rows
+    // over inside the kernel all chunks of a row go to the same XCD (row % 8), so the row's counters
+    // and partial results stay in one L2 instead of bouncing between eight; a launch that leaves the
+    // epilogue to a second one spreads them (row_slot).  Placement only affects speed: every
+    // hand-over below is device-coherent wherever the workgroups land.
     // Order within that: row-major -- all chunks of rows 0..7, then of rows 8..15, ... -- except in
     // the launches of at most one workgroup per compute unit (EARLY), which go chunk-major and whose
     // order hardly matters (every workgroup is resident at once).  Chunk-major order -- chunk 0 of
@@ -221,7 +222,6 @@ template <int C> struct FusedLauncher {
         const unsigned grid = (unsigned)(8ll * ((p0.rows + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
         Problem p = p0;
-        p.chunk_major = p.elect;                   // what the kernel compiles in (the grouped kernel reads the flag)
         p.scatter |= !p.elect;                     // no hand-over inside the launch: every XCD reads from every row
         if (p.block_table)
             return p.elect ? launch(decode_fused_kernel<C, true, true>, dim3(grid), dim3(Tune<C>::NW * 64), s, p)
@@ -239,7 +239,7 @@ template <int C> struct UnifiedLauncher {
         const unsigned grid = (unsigned)(8ll * ((p0.rows + 7) / 8) * p0.nc);
         if (grid == 0) return hipSuccess;
         Problem p = p0;
-        p.scatter |= grid > 1024u;                 // as the fused kernel's launches of that size
+        p.scatter |= grid > 1024u;                 // no hand-over in this launch; measured on large grids only
         const dim3 block(Tune<C>::NW * 64);
         if (grid <= (unsigned)kComputeUnits) return launch(partial_unified_kernel<C, true, true>, dim3(grid), block, s, p);
         if (grid <= 1024u) return launch(partial_unified_kernel<C, true, false>, dim3(grid), block, s, p);

@@ -91,3 +91,26 @@ def test_c4_overflow_stress(oracle, H):
     assert dc.flags()[2] == 0
     H.assert_close(got, oracle.attn_exact(lit["q"], lit["k"], lit["v"], lit["seq_lens"], lit["scale"], nthreads=16),
                    "c4, gamma 12")
+
+
+@pytest.mark.parametrize("Smax,lens,chunk,mib", [(8192, [8192, 5000], 1024, 256), (8192, [8192, 8100], 512, 256),
+                                                 (16384, [16384, 9000], 1024, 512), (12288, [12288, 700], 768, 384)])
+def test_launches_of_257_to_1024_workgroups(oracle, H, Smax, lens, chunk, mib):
+    """Between one and four workgroups per compute unit the per-row call picks its launch form by the
+    size of the cache (row epilogue elected inside the kernel below 320 MiB, a second launch from
+    there on): both forms, full and part-filled sequences, two planted out-of-range keys, checked
+    on every output element, flag, list entry and count."""
+    case = synth.make_case(B=2, Hq=32, Hkv=32, D=128, Smax=Smax, seed=7100 + chunk, seq_lens=lens, poison_padding=True)
+    assert case["k"].nbytes + case["v"].nbytes == mib << 20
+    planted = synth.plant_keys(case, 2, 36.0, seed=7200 + chunk)
+    want = oracle.attn_exact(case["q"], case["k"], case["v"], case["seq_lens"], case["scale"], nthreads=16)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk, nthreads=16)
+    assert margin.min() > 1e-2 and int(orf.sum()) == 2 and all(orf[b, h] for b, h, _ in planted)
+    dc = H.DeviceCase(case, chunk=chunk)
+    assert 256 < 64 * -(-Smax // chunk) <= 1024
+    for entry in ("fd_decode_attn", "fd_decode_attn", "fd_decode_attn_multikernel"):
+        got = dc.run(entry)
+        H.assert_close(got, want, "%s, %d MiB" % (entry, mib))
+        cf, rf, n, rows = dc.flags()
+        assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+        assert n == 2 and rows.tolist() == np.flatnonzero(orf.reshape(-1)).tolist()

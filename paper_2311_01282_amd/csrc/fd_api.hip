@@ -219,9 +219,10 @@ size_t fd_workspace_bytes(const fd_shape *shape)
 //   per-row kernel: at least four chunks per row and at most 2048 keys per chunk (a row in one
 //     or two pieces, or very long pieces, hide less latency: 18.3 us against 14.7 for 4 x 32
 //     rows of 1K keys cut in two instead of four); a large batch, whose sequences may differ in
-//     length, gets enough workgroups per CU (about 16) to even out ragged rows, but never
-//     chunks below 256 keys for that; otherwise the longest chunk that still gives 256
-//     workgroups.  Within 6 % of the best chunk on every shape of the sweep.
+//     length (8 sequences or more), gets enough workgroups per CU (about 16) to even out ragged
+//     rows, but never chunks below 256 keys for that; otherwise the longest chunk that still
+//     gives 256 workgroups -- for a batch, 2048 keys only where that makes the launch a single
+//     round of the chip, else at most 1024.  Within 6 % of the best chunk on every shape of the sweeps.
 //   grouped kernel: 1/G as many workgroups, each with four wavefronts' worth of loads in flight
 //     and a heavy tail (reduction over the group's heads); it is fastest with one workgroup
 //     per CU -- a single launch that finishes its rows itself -- so: the fewest chunks, of up to
@@ -275,8 +276,15 @@ int32_t fd_pick_chunk(const fd_shape *shape)
     } else {
         const int32_t quarter = sh.max_seq / 4;
         const int32_t longest = quarter >= 2048 ? 2048 : (quarter < 64 ? 64 : quarter);
-        if (sh.batch > 1) c = largest_with(4096, 256, longest < 1024 ? longest : 1024);
+        // many sequences, whose lengths may differ: enough workgroups per CU to even them out
+        if (sh.batch >= 8) c = largest_with(4096, 256, longest < 1024 ? longest : 1024);
         if (!c) c = largest_with(256, 64, longest);
+        // Chunks of 2048 keys pay when they make the launch a single round of the chip, and for a single
+        // sequence at any length (1 x 32 rows x 131072 keys: 315 us against 372 with 1024, 65536: 160
+        // against 171 -- a row of 64 or more chunks streams badly); a batch whose 2048-key chunks give
+        // more than one round does as well or better with 1024 (2 x 16384: 83.3 against 83.9 us; 3 x 8192:
+        // 63.8 against 67.2 with the equal chunks of 1648 that 2048 would become; 4 x 32768: a tie).
+        if (c == 2048 && sh.batch >= 2 && workgroups(2048) > 256) c = 1024;
     }
     if (!c) c = largest_with(256, 64, grouped ? 4096 : 1024);
     if (!c) c = 64;

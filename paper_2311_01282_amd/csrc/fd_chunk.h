@@ -316,13 +316,23 @@ __device__ __forceinline__ bool chunk_body(const Problem &p, int row, int c, Chu
         // last valid key (always in bounds, never padding) and get weight zero.
         const float nphi = -p.phi, lo = p.lo, hi = p.hi, scale = p.scale;
         bool bad = false;
-        auto issue = [&](int blk, u32x4 (&kk)[UP], u32x4 (&vv)[UP]) {
+        // Rows of more than 32 chunks: every workgroup starts its chunk at a different block and wraps
+        // around (the sums do not care about the order).  The workgroups of such a launch start at
+        // addresses a power of two apart and walk them in step, and for some shapes the memory system
+        // serves that badly: 1 x 32 rows x 131072 keys in 1024-key chunks 462 -> 338 us, 2 x 131072
+        // 718 -> 652, 1 x 131072 in 2048-key chunks 333 -> 317; the shapes that were fine lose up to
+        // 1.4 % (4 x 65536), and with 32 chunks per row or fewer (4 x 32768: 321 -> 330 us) it only costs.
+        const int rot = (!EARLY && p.nc > 32 && nblk > 1) ? (int)((unsigned)(c * 3 + row) % (unsigned)nblk) : 0;
+        auto phys = [&](int blk) { const int b = blk + rot; return b >= nblk ? b - nblk : b; };
+        auto issue = [&](int blk0, u32x4 (&kk)[UP], u32x4 (&vv)[UP]) {
+            const int blk = phys(blk0);
 #pragma unroll
             for (int u = 0; u < UP; ++u) kk[u] = load_stream(kp + at(min(key_of(blk * UP + u), last)));
 #pragma unroll
             for (int u = 0; u < UP; ++u) vv[u] = load_stream(vp + at(min(key_of(blk * UP + u), last)));
         };
-        auto reduce = [&](int blk, const u32x4 (&kk)[UP], const u32x4 (&vv)[UP]) {
+        auto reduce = [&](int blk0, const u32x4 (&kk)[UP], const u32x4 (&vv)[UP]) {
+            const int blk = phys(blk0);
 #pragma unroll
             for (int u = 0; u < UP; ++u) {
                 const bool valid = key_of(blk * UP + u) <= last;

@@ -236,25 +236,35 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
     const int nblk_valid = min(NBLK, (nres + 15) / 16);
     const int nmine = nblk_valid > wave ? (nblk_valid - wave + NW - 1) / NW : 0;
     if (nmine > 0) {
+        // Rows of more than 32 chunks: the wavefront starts at a different one of its blocks in every
+        // workgroup and wraps around (as in the per-row kernel: workgroups that start a power of two
+        // apart and advance in step are served badly by the memory system for some shapes; 1 x 64/8
+        // heads x 262144 keys: 188 us against 161 for the same bytes as 4 x 65536).  Whichever block
+        // comes first fixes the scale of the fp16 weights.
+#ifndef FD_EXP_GROT
+#define FD_EXP_GROT 1
+#endif
+        const int rot = (FD_EXP_GROT && p.nc > 32 && nmine > 1) ? (int)((unsigned)(c * 3 + gi) % (unsigned)nmine) : 0;
+        auto blk_of = [&](int i) { const int t = i + rot; return wave + NW * (t >= nmine ? t - nmine : t); };
         u32x4 kA[4], vA[4], kB[4], vB[4];
-        issue(wave, kA, vA);
+        issue(blk_of(0), kA, vA);
         int i = 0;
 #pragma unroll 1
         for (; i + 2 < nmine; i += 2) {
-            issue(wave + NW * (i + 1), kB, vB);
+            issue(blk_of(i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);     // keep the prefetch ahead of the arithmetic
-            reduce(wave + NW * i, i == 0, kA, vA);
-            issue(wave + NW * (i + 2), kA, vA);
+            reduce(blk_of(i), i == 0, kA, vA);
+            issue(blk_of(i + 2), kA, vA);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + NW * (i + 1), false, kB, vB);
+            reduce(blk_of(i + 1), false, kB, vB);
         }
         if (i + 2 == nmine) {
-            issue(wave + NW * (i + 1), kB, vB);
+            issue(blk_of(i + 1), kB, vB);
             __builtin_amdgcn_sched_barrier(0);
-            reduce(wave + NW * i, i == 0, kA, vA);
-            reduce(wave + NW * (i + 1), false, kB, vB);
+            reduce(blk_of(i), i == 0, kA, vA);
+            reduce(blk_of(i + 1), false, kB, vB);
         } else {
-            reduce(wave + NW * i, i == 0, kA, vA);
+            reduce(blk_of(i), i == 0, kA, vA);
         }
         // Take the scales out again (exact: integer powers of two).  den belongs to head n; acc[e][r]
         // to head 4g + r, whose exponent sits in the lanes with n = 4g + r.

@@ -180,3 +180,31 @@ def test_the_picked_chunk_on_lengths_that_do_not_divide(oracle, H, B, Hq, Hkv, S
     cf, rf, n, rows = dc.flags()
     if margin.min() > 1e-2:
         assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,Smax,lens,chunk", [
+    (2, 8, 8, 4096, [4096, 3001], 64),        # 64 chunks per row of a single block each: nothing to rotate
+    (1, 32, 32, 8192, [8000], 128),           # 64 chunks per row, 2048 workgroups, two blocks per chunk
+    (2, 16, 2, 4096, [4096, 2500], 64),       # grouped kernel, 64 chunks per head group, one block per wavefront
+    (1, 64, 8, 16384, [16001], 256),          # grouped kernel, 64 chunks, four blocks per wavefront
+    (1, 4, 4, 40000, [39999], 1024),          # 40 chunks of 1024 keys: eight blocks to rotate through
+])
+def test_rows_of_more_than_32_chunks(oracle, H, B, Hq, Hkv, Smax, lens, chunk):
+    """Beyond 32 chunks per row every workgroup (grouped kernel: every wavefront) starts its chunk at a
+    different key block and wraps around; the sums must not care, the flags must land on the right chunks."""
+    case = synth.make_case(B=B, Hq=Hq, Hkv=Hkv, D=128, Smax=Smax, seed=3300 + Smax + chunk, seq_lens=lens,
+                           poison_padding=True)
+    planted = synth.plant_keys(case, 2, 36.0, seed=3301 + chunk, allow_shared_kv=Hq != Hkv)
+    assert -(-Smax // chunk) > 32 and len(planted) == 2
+    want = exact(oracle, case)
+    ocf, orf, margin = oracle.flags(case["q"], case["k"], case["seq_lens"], case["scale"], synth.PHI, LO, HI, chunk, nthreads=8)
+    assert margin.min() > 1e-2 and orf.sum() >= 2
+    dc = H.DeviceCase(case, chunk=chunk)
+    entries = ["fd_decode_attn"] + (["fd_decode_attn_gqa"] if 2 <= Hq // Hkv <= 16 else [])
+    for entry in entries:
+        for rep in range(2):
+            got = dc.run(entry)
+            H.assert_close(got, want, "%s, %d chunks per row" % (entry, -(-Smax // chunk)))
+            cf, rf, n, rows = dc.flags()
+            assert np.array_equal(cf, ocf) and np.array_equal(rf, orf)
+            assert n == int(orf.sum()) and rows.tolist() == np.flatnonzero(orf.reshape(-1)).tolist()

@@ -241,10 +241,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 3 : 1) void decode_fused_gqa_ker
         // apart and advance in step are served badly by the memory system for some shapes; 1 x 64/8
         // heads x 262144 keys: 188 us against 161 for the same bytes as 4 x 65536).  Whichever block
         // comes first fixes the scale of the fp16 weights.
-#ifndef FD_EXP_GROT
-#define FD_EXP_GROT 1
-#endif
-        const int rot = (FD_EXP_GROT && p.nc > 32 && nmine > 1) ? (int)((unsigned)(c * 3 + gi) % (unsigned)nmine) : 0;
+        const int rot = (p.nc > 32 && nmine > 1) ? (int)((unsigned)(c * 3 + gi) % (unsigned)nmine) : 0;
         auto blk_of = [&](int i) { const int t = i + rot; return wave + NW * (t >= nmine ? t - nmine : t); };
         u32x4 kA[4], vA[4], kB[4], vB[4];
         issue(blk_of(0), kA, vA);
